@@ -1,0 +1,160 @@
+/*
+ * lamina_attn.h -- C ABI of the MI355X (gfx950) decode attention operator.
+ *
+ * The operator is the attention step that model-attention disaggregation places on the
+ * memory-optimised device that owns the KV cache (paper Sec. 3.1, Sec. 2.2.2): per
+ * decode iteration and layer it receives one query vector per in-flight request and
+ * query head, and returns one output vector per request and query head,
+ *
+ *     out[r][h] = sum_j softmax_j( scale * <q[r][h], K[r][g][j]> ) * V[r][g][j],
+ *     j = 0 .. seq_lens[r]-1,   g = h div G,   G = num_q_heads / num_kv_heads
+ *
+ * (Sec. 2.1, the starred equation; grouped-query attention as in Sec. 2.2.2: the G query
+ * heads of a group read the same K/V and their outputs are concatenated), together with
+ * lse[r][h] = ln sum_j exp(scale * <q, K_j>), the natural logarithm of the softmax
+ * denominator S_q(I) of Sec. 4.2.2, so that results over disjoint token sets can be
+ * combined by the divide-and-conquer identity of that section.
+ *
+ * All tensor pointers are DEVICE pointers owned by the caller; the library never frees
+ * or reallocates them and never copies them to the host.  Calls only enqueue kernels on
+ * the given HIP stream and return; they do not synchronise.  Functions return LAMINA_OK
+ * (0) or a negative error code; nothing aborts and no C++ exception crosses the ABI.
+ */
+#ifndef LAMINA_ATTN_H
+#define LAMINA_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lamina_attn *lamina_attn_t;            /* opaque handle */
+
+enum {
+    LAMINA_OK              =  0,
+    LAMINA_ERR_INVALID_ARG = -1,   /* NULL/ill-formed argument; nothing was launched      */
+    LAMINA_ERR_UNSUPPORTED = -2,   /* well-formed but outside what the kernels cover      */
+    LAMINA_ERR_HIP         = -3,   /* a HIP runtime call failed; see lamina_attn_last_error */
+    LAMINA_ERR_WORKSPACE   = -4    /* the split-KV workspace could not be allocated       */
+};
+
+enum { LAMINA_BF16 = 0, LAMINA_FP8_E4M3 = 1, LAMINA_F32 = 2 };
+
+/* Kernel family used for the main pass.  Both compute the same function. */
+enum {
+    LAMINA_KERNEL_MFMA = 0,        /* default: matrix-core tiles for q.K^T and p.V          */
+    LAMINA_KERNEL_VALU = 1         /* plain vector-ALU kernel, kept for A/B measurements    */
+};
+
+/*
+ * Fixed properties of one attention layer-share, given at creation.
+ * head_dim must be 128.  num_q_heads must be a multiple of num_kv_heads and the group
+ * size G = num_q_heads / num_kv_heads must be one of 1, 2, 4, 8, 16.
+ */
+typedef struct {
+    int32_t num_q_heads;
+    int32_t num_kv_heads;
+    int32_t head_dim;
+    int32_t kv_dtype;       /* LAMINA_BF16, or LAMINA_FP8_E4M3 (OCP e4m3fn bytes + fp32 scales) */
+    int32_t out_dtype;      /* LAMINA_BF16 or LAMINA_F32                                        */
+    int32_t block_size;     /* 0: contiguous strided cache; 16: paged cache with a block table  */
+    int32_t max_batch;      /* upper bound on `batch` of any call; sizes grid and workspace     */
+    int32_t max_seq_len;    /* upper bound on any seq_lens[r]; sizes the split-KV partition     */
+    int32_t num_splits;     /* 0: library chooses; 1: never split; N>1: exactly N partitions of
+                               ceil(max_seq_len / N) tokens (rounded up to a multiple of 64)    */
+    float   softmax_scale;  /* 0 means 1/sqrt(head_dim)                                         */
+    int32_t device;         /* HIP device ordinal the handle is bound to                        */
+    int32_t kernel;         /* LAMINA_KERNEL_MFMA or LAMINA_KERNEL_VALU                         */
+} lamina_attn_config;
+
+/*
+ * Per-call arguments that are not tensors.  Strides are in ELEMENTS of the cache dtype;
+ * the innermost (head_dim) stride is always 1 and every row start must be 16-byte aligned.
+ */
+typedef struct {
+    int32_t batch;               /* R: requests in this call, 0 <= R <= max_batch              */
+    int64_t kv_stride_req;       /* contiguous mode: distance between requests                 */
+    int64_t kv_stride_head;      /* contiguous mode: distance between kv heads                 */
+    int64_t kv_stride_tok;       /* contiguous mode: distance between tokens (>= head_dim)     */
+    int64_t pool_stride_block;   /* paged mode: distance between pool blocks                   */
+    int64_t pool_stride_head;    /* paged mode: distance between kv heads inside a block;
+                                    tokens of one (block, head) are block_size rows of head_dim */
+    int32_t block_table_stride;  /* paged mode: entries per request row of block_table         */
+    const float *k_scale;        /* device [R][num_kv_heads]; fp8 only, else NULL              */
+    const float *v_scale;        /* device [R][num_kv_heads]; fp8 only, else NULL              */
+    void *stream;                /* hipStream_t; NULL = the default stream                     */
+} lamina_call_params;
+
+/*
+ * Create a handle for one layer-share on cfg->device.  Validates cfg, picks the split-KV
+ * partitioning and allocates the handle-owned workspace for partial results
+ * ([max_batch][num_q_heads][splits][head_dim + 1] fp32; nothing when splits == 1).
+ * On success *out_handle is set.  Errors: INVALID_ARG (NULL, non-positive sizes,
+ * num_q_heads % num_kv_heads != 0, unknown dtype), UNSUPPORTED (head_dim != 128,
+ * block_size not in {0, 16}, group size not in {1,2,4,8,16}), HIP, WORKSPACE.
+ */
+int lamina_attn_create(const lamina_attn_config *cfg, lamina_attn_t *out_handle);
+
+/*
+ * One decode-attention call (Sec. 2.1 starred equation per request and head; split-KV
+ * partials merged by the identity of Sec. 4.2.2 when the handle uses more than one
+ * partition).
+ *
+ *   q            device bf16  [R][num_q_heads][128], dense
+ *   k_cache      device; contiguous mode: rows K[r][g][j][0..127] at
+ *                r*kv_stride_req + g*kv_stride_head + j*kv_stride_tok;
+ *                paged mode: pool, token j of request r lives in pool block
+ *                block_table[r][j / 16] at row j % 16:
+ *                blk*pool_stride_block + g*pool_stride_head + (j%16)*128
+ *   v_cache      device; same dtype and layout as k_cache
+ *   seq_lens     device int32 [R]: tokens to attend, INCLUDING the token being decoded
+ *                (whose k, v the caller has already written).  Values above max_seq_len
+ *                are not checked and give undefined results.  Never read by the host.
+ *   block_table  device int32 [R][block_table_stride]; only entries below
+ *                ceil(seq_lens[r]/16) are read.  NULL in contiguous mode.
+ *   out          device [R][num_q_heads][128] of out_dtype, dense
+ *   lse          device fp32 [R][num_q_heads], or NULL if not wanted
+ *
+ * fp8 caches hold OCP e4m3fn bytes; the value of an element is decode(byte) * k_scale[r][g]
+ * (resp. v_scale[r][g]).  Rows at or beyond seq_lens[r], the tail of a request's last
+ * block and unreferenced pool blocks may hold anything (including NaN patterns).
+ * seq_lens[r] == 0 gives out[r] = 0 and lse[r] = -inf.
+ *
+ * Errors (nothing is launched): INVALID_ARG for a NULL handle/params/required pointer,
+ * batch < 0 or > max_batch, paged mode without block_table, fp8 without scales, strides
+ * that break the alignment rule; HIP if a launch fails.  batch == 0 is a no-op.
+ * One handle must not be used from two streams at once (they would share the workspace).
+ */
+int lamina_decode_attention(lamina_attn_t h,
+                            const void *q,
+                            const void *k_cache,
+                            const void *v_cache,
+                            const int32_t *seq_lens,
+                            const int32_t *block_table,
+                            void *out,
+                            float *lse,
+                            const lamina_call_params *p);
+
+/* Free the handle and its workspace.  NULL is accepted.  Does not synchronise: the caller
+ * makes sure no call on this handle is still running. */
+int lamina_attn_destroy(lamina_attn_t h);
+
+/* Message for the last error on this handle (or, with h == NULL, for the last failed
+ * lamina_attn_create on this thread).  Owned by the library; valid until the next call. */
+const char *lamina_attn_last_error(lamina_attn_t h);
+
+/* Bytes of device workspace a handle made from cfg would own (0 when unsplit), or 0 if
+ * cfg is invalid.  Does not touch the GPU. */
+size_t lamina_attn_workspace_bytes(const lamina_attn_config *cfg);
+
+/* Partitioning chosen at creation: number of KV partitions per request (>= 1) and the
+ * tokens per partition.  Used by callers that account for the partial-result traffic. */
+int lamina_attn_num_splits(lamina_attn_t h);
+int lamina_attn_split_tokens(lamina_attn_t h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAMINA_ATTN_H */

@@ -1,0 +1,199 @@
+"""ctypes binding over the C ABI of ``include/lamina_attn.h``.
+
+Argument marshalling only: every step of the operator runs in the HIP kernels of
+``liblamina_attn.so``.  PyTorch appears only as the owner of device memory and streams.
+There is no CPU fallback: if the library is missing and cannot be built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import shutil
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+_SRC = os.path.join(_HERE, "csrc", "lamina_attn.hip")
+_INC = os.path.join(_ROOT, "include")
+LIB_PATH = os.path.join(_HERE, "liblamina_attn.so")
+
+LAMINA_OK = 0
+LAMINA_ERR_INVALID_ARG = -1
+LAMINA_ERR_UNSUPPORTED = -2
+LAMINA_ERR_HIP = -3
+LAMINA_ERR_WORKSPACE = -4
+LAMINA_BF16, LAMINA_FP8_E4M3, LAMINA_F32 = 0, 1, 2
+LAMINA_KERNEL_MFMA, LAMINA_KERNEL_VALU = 0, 1
+
+EXPORTS = ("lamina_attn_create", "lamina_decode_attention", "lamina_attn_destroy",
+           "lamina_attn_last_error", "lamina_attn_workspace_bytes", "lamina_attn_num_splits",
+           "lamina_attn_split_tokens")
+
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+class lamina_attn_config(ctypes.Structure):
+    _fields_ = [("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("kv_dtype", ctypes.c_int32),
+                ("out_dtype", ctypes.c_int32), ("block_size", ctypes.c_int32),
+                ("max_batch", ctypes.c_int32), ("max_seq_len", ctypes.c_int32),
+                ("num_splits", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("device", ctypes.c_int32), ("kernel", ctypes.c_int32)]
+
+
+class lamina_call_params(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32),
+                ("kv_stride_req", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64),
+                ("kv_stride_tok", ctypes.c_int64),
+                ("pool_stride_block", ctypes.c_int64), ("pool_stride_head", ctypes.c_int64),
+                ("block_table_stride", ctypes.c_int32),
+                ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
+                ("stream", ctypes.c_void_p)]
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile the HIP library for gfx950 in-tree with hipcc; returns its path."""
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", _INC, "-o", LIB_PATH, _SRC]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    if verbose:
+        print(" ".join(cmd))
+    return LIB_PATH
+
+
+_lib = None
+
+
+def load():
+    """Load the built library (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        build_library()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp = ctypes.c_void_p
+    lib.lamina_attn_create.restype = ctypes.c_int
+    lib.lamina_attn_create.argtypes = [ctypes.POINTER(lamina_attn_config), ctypes.POINTER(vp)]
+    lib.lamina_decode_attention.restype = ctypes.c_int
+    lib.lamina_decode_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp,
+                                            ctypes.POINTER(lamina_call_params)]
+    lib.lamina_attn_destroy.restype = ctypes.c_int
+    lib.lamina_attn_destroy.argtypes = [vp]
+    lib.lamina_attn_last_error.restype = ctypes.c_char_p
+    lib.lamina_attn_last_error.argtypes = [vp]
+    lib.lamina_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.lamina_attn_workspace_bytes.argtypes = [ctypes.POINTER(lamina_attn_config)]
+    lib.lamina_attn_num_splits.restype = ctypes.c_int
+    lib.lamina_attn_num_splits.argtypes = [vp]
+    lib.lamina_attn_split_tokens.restype = ctypes.c_int
+    lib.lamina_attn_split_tokens.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+class LaminaError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"lamina error {code}: {msg}")
+        self.code = code
+
+
+# ---- same names as the C ABI -------------------------------------------------------------
+
+def lamina_attn_create(cfg: lamina_attn_config):
+    """Returns (status, handle).  handle is a c_void_p (None-valued on failure)."""
+    h = ctypes.c_void_p()
+    rc = load().lamina_attn_create(ctypes.byref(cfg), ctypes.byref(h))
+    return rc, h
+
+
+def lamina_decode_attention(h, q, k_cache, v_cache, seq_lens, block_table, out, lse,
+                            params: lamina_call_params) -> int:
+    """Pointers are integers (device addresses) or None."""
+    return load().lamina_decode_attention(h, q, k_cache, v_cache, seq_lens, block_table, out,
+                                          lse, ctypes.byref(params) if params is not None else None)
+
+
+def lamina_attn_destroy(h) -> int:
+    return load().lamina_attn_destroy(h)
+
+
+def lamina_attn_last_error(h=None) -> str:
+    s = load().lamina_attn_last_error(h)
+    return s.decode() if s else ""
+
+
+def lamina_attn_workspace_bytes(cfg: lamina_attn_config) -> int:
+    return int(load().lamina_attn_workspace_bytes(ctypes.byref(cfg)))
+
+
+# ---- convenience wrapper over torch tensors ---------------------------------------------
+
+_DTYPES = {"bf16": LAMINA_BF16, "fp8": LAMINA_FP8_E4M3, "f32": LAMINA_F32}
+
+
+class DecodeAttention:
+    """One handle = one attention layer-share.  Tensors are torch CUDA tensors."""
+
+    def __init__(self, num_q_heads, num_kv_heads, max_batch, max_seq_len, *, kv_dtype="bf16",
+                 out_dtype="f32", block_size=0, num_splits=0, softmax_scale=0.0, device=0,
+                 head_dim=128, kernel=LAMINA_KERNEL_MFMA):
+        self.cfg = lamina_attn_config(num_q_heads, num_kv_heads, head_dim, _DTYPES[kv_dtype],
+                                      _DTYPES[out_dtype], block_size, max_batch, max_seq_len,
+                                      num_splits, softmax_scale, device, kernel)
+        rc, self.handle = lamina_attn_create(self.cfg)
+        if rc != LAMINA_OK:
+            self.handle = None
+            raise LaminaError(rc, lamina_attn_last_error(None))
+        self.out_dtype = out_dtype
+        self.num_splits = int(load().lamina_attn_num_splits(self.handle))
+        self.split_tokens = int(load().lamina_attn_split_tokens(self.handle))
+
+    def close(self):
+        if getattr(self, "handle", None) is not None:
+            lamina_attn_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def params_for(self, q, k_cache, block_table=None, k_scale=None, v_scale=None, stream=None):
+        import torch
+        p = lamina_call_params()
+        p.batch = q.shape[0]
+        if self.cfg.block_size:
+            p.pool_stride_block, p.pool_stride_head = k_cache.stride(0), k_cache.stride(1)
+            p.block_table_stride = block_table.stride(0)
+        else:
+            p.kv_stride_req, p.kv_stride_head, p.kv_stride_tok = (
+                k_cache.stride(0), k_cache.stride(1), k_cache.stride(2))
+        p.k_scale = k_scale.data_ptr() if k_scale is not None else None
+        p.v_scale = v_scale.data_ptr() if v_scale is not None else None
+        if stream is None:
+            stream = torch.cuda.current_stream(q.device)
+        p.stream = stream.cuda_stream or None
+        return p
+
+    def __call__(self, q, k_cache, v_cache, seq_lens, block_table=None, k_scale=None,
+                 v_scale=None, out=None, lse=None, stream=None, want_lse=True):
+        import torch
+        R, Hq, D = q.shape
+        if out is None:
+            out = torch.empty((R, Hq, D), device=q.device,
+                              dtype=torch.float32 if self.out_dtype == "f32" else torch.bfloat16)
+        if lse is None and want_lse:
+            lse = torch.empty((R, Hq), device=q.device, dtype=torch.float32)
+        p = self.params_for(q, k_cache, block_table, k_scale, v_scale, stream)
+        rc = lamina_decode_attention(
+            self.handle, q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(),
+            seq_lens.data_ptr(), block_table.data_ptr() if block_table is not None else None,
+            out.data_ptr(), lse.data_ptr() if lse is not None else None, p)
+        if rc != LAMINA_OK:
+            raise LaminaError(rc, lamina_attn_last_error(self.handle))
+        return out, lse

@@ -1,0 +1,330 @@
+"""Parity of the HIP library (through its C ABI) with the fp64 CPU oracle, element by
+element on the same seeded inputs.  Tolerances (stated with the target of this build):
+
+* bf16 cache, fp32 accumulate, fp32 output: max |gpu - ref| <= 2e-3 over all elements and
+  max |gpu - ref| / |ref| <= 1e-2 over elements with |ref| >= 1e-3;
+* bf16 output: |gpu - ref| <= 2e-3 + 1e-2 |ref| (half an ulp of bf16 exceeds 2e-3 above 1);
+* fp8 cache: max |gpu - ref| <= 3e-2 against the oracle on the same dequantised values;
+* lse: 1e-3 absolute (5e-3 for fp8).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2405_01814_amd import lamina, workloads as W
+
+pytestmark = pytest.mark.gpu
+SCALE = 1.0 / math.sqrt(128)
+
+
+def dev():
+    assert torch.cuda.is_available()
+    return torch.device("cuda:0")
+
+
+def oracle_of(b, pairs=None):
+    w = b["workload"]
+    return oracle.decode_attention(
+        b["q"], b["k"], b["v"], b["seq_lens"], num_kv_heads=w.num_kv_heads, scale=SCALE,
+        block_table=b.get("block_table"), block_size=w.block_size,
+        k_scale=b.get("k_scale"), v_scale=b.get("v_scale"), pairs=pairs)
+
+
+def gpu_of(b, out_dtype="f32", num_splits=None, max_seq_len=None, max_batch=None, reps=1):
+    w = b["workload"]
+    d = dev()
+    R = b["q"].shape[0]
+    op = lamina.DecodeAttention(
+        w.num_q_heads, w.num_kv_heads, max_batch=max_batch or max(R, 1),
+        max_seq_len=max_seq_len or max(b["max_seq_len"], 1), kv_dtype=w.kv_dtype,
+        out_dtype=out_dtype, block_size=w.block_size,
+        num_splits=w.num_splits if num_splits is None else num_splits)
+    t = {k: v.to(d) for k, v in b.items() if isinstance(v, torch.Tensor)}
+    outs = []
+    for _ in range(reps):
+        out, lse = op(t["q"], t["k"], t["v"], t["seq_lens"], block_table=t.get("block_table"),
+                      k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))
+        torch.cuda.synchronize()
+        outs.append((out.float().cpu().double().numpy(), lse.cpu().double().numpy()))
+    info = (op.num_splits, op.split_tokens)
+    op.close()
+    return outs if reps > 1 else outs[0], info
+
+
+def check(got, ref, kind, pairs=None):
+    out, lse = got
+    ref_out, ref_lse = ref
+    if pairs is not None:
+        pr = np.asarray(pairs)
+        out, lse = out[pr[:, 0], pr[:, 1]], lse[pr[:, 0], pr[:, 1]]
+    assert np.isfinite(out).all(), "non-finite output (poisoned padding was read?)"
+    err = np.abs(out - ref_out)
+    fin = np.isfinite(ref_lse)
+    assert (lse[~fin] == ref_lse[~fin]).all()
+    lerr = np.abs(lse[fin] - ref_lse[fin]).max() if fin.any() else 0.0
+    if kind == "bf16_f32":
+        big = np.abs(ref_out) >= 1e-3
+        rel = (err[big] / np.abs(ref_out[big])).max() if big.any() else 0.0
+        assert err.max() <= 2e-3, f"max abs {err.max():.3e}"
+        assert rel <= 1e-2, f"max rel {rel:.3e}"
+        assert lerr <= 1e-3, f"lse {lerr:.3e}"
+    elif kind == "bf16_bf16":
+        assert (err <= 2e-3 + 1e-2 * np.abs(ref_out)).all(), f"max abs {err.max():.3e}"
+        assert lerr <= 1e-3
+    elif kind == "fp8":
+        assert err.max() <= 3e-2, f"max abs {err.max():.3e}"
+        assert lerr <= 5e-3, f"lse {lerr:.3e}"
+    else:
+        raise ValueError(kind)
+    return float(err.max()), float(lerr)
+
+
+def sized(name, lens, **over):
+    w = W.WORKLOADS[name]
+    if over:
+        import dataclasses
+        w = dataclasses.replace(w, **over)
+    return W.generate(w, lens=np.asarray(lens, dtype=np.int32))
+
+
+# ---- the named workloads at sizes the oracle finishes in seconds ---------------------------
+
+def test_tiny_workload_matches_oracle():
+    b = W.generate(W.WORKLOADS["tiny"])
+    got, _ = gpu_of(b)
+    check(got, oracle_of(b), "bf16_f32")
+
+
+RAGGED = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 1000, 4101]
+
+
+@pytest.mark.parametrize("splits", [1, 0, 3, 40])
+def test_ragged_lengths_contiguous_bf16(splits):
+    b = sized("llama3_8b_ctx4096", RAGGED)
+    got, info = gpu_of(b, num_splits=splits)
+    check(got, oracle_of(b), "bf16_f32")
+    if splits > 1:
+        assert info[0] == splits
+
+
+def test_bf16_output_type():
+    b = sized("llama3_8b_ctx4096", [300, 4096, 77])
+    got, _ = gpu_of(b, out_dtype="bf16")
+    check(got, oracle_of(b), "bf16_bf16")
+
+
+@pytest.mark.parametrize("name,G", [("llama3_8b_ctx4096", 4), ("llama3_70b_headshare_paged", 8)])
+def test_group_sizes_of_the_named_models(name, G):
+    assert W.WORKLOADS[name].group == G
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 8), (8, 4), (16, 1), (4, 1)])
+def test_other_group_sizes(hq, hkv):
+    b = sized("llama3_8b_ctx4096", [200, 515, 64], num_q_heads=hq, num_kv_heads=hkv)
+    got, _ = gpu_of(b)
+    check(got, oracle_of(b), "bf16_f32")
+
+
+@pytest.mark.parametrize("splits", [1, 0, 5])
+def test_paged_bf16_with_shuffled_block_table(splits):
+    lens = [1, 16, 17, 100, 128, 2049, 700, 31, 3333, 4096, 513, 15]
+    b = sized("llama3_70b_headshare_paged", lens)
+    got, _ = gpu_of(b, num_splits=splits)
+    check(got, oracle_of(b), "bf16_f32")
+
+
+@pytest.mark.parametrize("splits", [1, 0, 6])
+def test_fp8_paged(splits):
+    lens = [1024, 1, 17, 2000, 129, 5000, 64, 3071]
+    b = sized("fp8_paged", lens)
+    got, _ = gpu_of(b, num_splits=splits)
+    check(got, oracle_of(b), "fp8")
+
+
+def test_fp8_contiguous():
+    b = sized("fp8_paged", [33, 700, 1], block_size=0)
+    got, _ = gpu_of(b)
+    check(got, oracle_of(b), "fp8")
+
+
+def test_split_kv_64_partitions_including_requests_shorter_than_the_split_count():
+    # 64 partitions of 128 tokens over max_seq_len 8192; several requests leave most empty
+    lens = [8192, 1, 127, 128, 129, 5000, 64, 8191]
+    b = sized("longctx_split64", lens)
+    got, info = gpu_of(b)
+    assert info == (64, 128)
+    check(got, oracle_of(b), "bf16_f32")
+
+
+def test_empty_context_and_empty_batch():
+    b = sized("llama3_8b_ctx4096", [0, 5, 0, 300])
+    for splits in (1, 4):
+        got, _ = gpu_of(b, num_splits=splits, max_seq_len=512)
+        out, lse = got
+        assert (out[0] == 0).all() and (out[2] == 0).all()
+        assert np.isneginf(lse[0]).all() and np.isneginf(lse[2]).all()
+        check(got, oracle_of(b), "bf16_f32")
+    # batch == 0 is a no-op that must not touch the GPU buffers
+    op = lamina.DecodeAttention(32, 8, max_batch=4, max_seq_len=64)
+    p = lamina.lamina_call_params()
+    p.batch = 0
+    assert lamina.lamina_decode_attention(op.handle, None, None, None, None, None, None, None,
+                                          p) == lamina.LAMINA_OK
+    op.close()
+
+
+def test_results_are_bitwise_reproducible_run_to_run():
+    b = sized("llama3_8b_ctx4096", [4096, 1000, 37, 2222])
+    for splits in (1, 8):
+        runs, _ = gpu_of(b, num_splits=splits, reps=3)
+        for o, l in runs[1:]:
+            assert np.array_equal(o, runs[0][0]) and np.array_equal(l, runs[0][1])
+
+
+def test_larger_capacity_than_the_call_uses():
+    # max_batch / max_seq_len above what the call needs: same numbers
+    b = sized("llama3_8b_ctx4096", [700, 90])
+    got, _ = gpu_of(b, max_batch=64, max_seq_len=4096)
+    check(got, oracle_of(b), "bf16_f32")
+
+
+def test_strided_cache_view():
+    b = sized("llama3_8b_ctx4096", [130, 257])
+    w = b["workload"]
+    d = dev()
+    R, Hkv, L, D = b["k"].shape
+    bigk = torch.full((R, Hkv, L + 7, 2 * D), float("nan"), dtype=torch.bfloat16)
+    bigv = torch.full((R, Hkv, L + 7, 2 * D), float("nan"), dtype=torch.bfloat16)
+    bigk[:, :, :L, :D] = b["k"]
+    bigv[:, :, :L, :D] = b["v"]
+    op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=R, max_seq_len=L)
+    out, lse = op(b["q"].to(d), bigk.to(d)[:, :, :, :D], bigv.to(d)[:, :, :, :D],
+                  b["seq_lens"].to(d))
+    torch.cuda.synchronize()
+    check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b), "bf16_f32")
+    op.close()
+
+
+def test_call_argument_errors_are_reported_not_launched():
+    d = dev()
+    op = lamina.DecodeAttention(32, 8, max_batch=2, max_seq_len=64)
+    q = torch.zeros(2, 32, 128, dtype=torch.bfloat16, device=d)
+    k = torch.zeros(2, 8, 64, 128, dtype=torch.bfloat16, device=d)
+    lens = torch.ones(2, dtype=torch.int32, device=d)
+    out = torch.zeros(2, 32, 128, device=d)
+
+    def call(batch=2, qq=q, kk=k, stride_tok=128, oo=out):
+        p = lamina.lamina_call_params()
+        p.batch = batch
+        p.kv_stride_req, p.kv_stride_head, p.kv_stride_tok = 8 * 64 * 128, 64 * 128, stride_tok
+        return lamina.lamina_decode_attention(
+            op.handle, qq.data_ptr() if qq is not None else None,
+            kk.data_ptr() if kk is not None else None, k.data_ptr(), lens.data_ptr(), None,
+            oo.data_ptr() if oo is not None else None, None, p)
+
+    assert call() == lamina.LAMINA_OK
+    assert call(batch=3) == lamina.LAMINA_ERR_INVALID_ARG
+    assert "max_batch" in lamina.lamina_attn_last_error(op.handle)
+    assert call(batch=-1) == lamina.LAMINA_ERR_INVALID_ARG
+    assert call(qq=None) == lamina.LAMINA_ERR_INVALID_ARG
+    assert call(kk=None) == lamina.LAMINA_ERR_INVALID_ARG
+    assert call(oo=None) == lamina.LAMINA_ERR_INVALID_ARG
+    assert call(stride_tok=100) == lamina.LAMINA_ERR_INVALID_ARG
+    assert call(stride_tok=132) == lamina.LAMINA_ERR_INVALID_ARG        # rows not 16 B aligned
+    assert lamina.lamina_decode_attention(op.handle, q.data_ptr(), k.data_ptr(), k.data_ptr(),
+                                          lens.data_ptr(), None, out.data_ptr(), None,
+                                          None) == lamina.LAMINA_ERR_INVALID_ARG
+    op.close()
+    # paged without a block table, fp8 without scales
+    op = lamina.DecodeAttention(8, 1, max_batch=2, max_seq_len=64, block_size=16)
+    p = lamina.lamina_call_params()
+    p.batch, p.pool_stride_block, p.pool_stride_head, p.block_table_stride = 2, 2048, 2048, 4
+    assert lamina.lamina_decode_attention(op.handle, q.data_ptr(), k.data_ptr(), k.data_ptr(),
+                                          lens.data_ptr(), None, out.data_ptr(), None,
+                                          p) == lamina.LAMINA_ERR_INVALID_ARG
+    op.close()
+    op = lamina.DecodeAttention(8, 1, max_batch=2, max_seq_len=64, kv_dtype="fp8")
+    p = lamina.lamina_call_params()
+    p.batch, p.kv_stride_req, p.kv_stride_head, p.kv_stride_tok = 2, 8192, 8192, 128
+    assert lamina.lamina_decode_attention(op.handle, q.data_ptr(), k.data_ptr(), k.data_ptr(),
+                                          lens.data_ptr(), None, out.data_ptr(), None,
+                                          p) == lamina.LAMINA_ERR_INVALID_ARG
+    op.close()
+    torch.cuda.synchronize()
+
+
+def test_non_default_stream():
+    b = sized("llama3_8b_ctx4096", [900, 64])
+    w = b["workload"]
+    d = dev()
+    t = {k: v.to(d) for k, v in b.items() if isinstance(v, torch.Tensor)}
+    op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=2, max_seq_len=1024,
+                                num_splits=4)
+    s = torch.cuda.Stream(device=d)
+    s.wait_stream(torch.cuda.current_stream(d))
+    with torch.cuda.stream(s):
+        out, lse = op(t["q"], t["k"], t["v"], t["seq_lens"])
+    s.synchronize()
+    check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b), "bf16_f32")
+    op.close()
+
+
+# ---- the named workloads at full size, in the launch configuration bench.py times ----------
+
+def sample_pairs(b, n, seed):
+    R, Hq = b["q"].shape[:2]
+    rng = np.random.default_rng(seed)
+    lens = b["seq_lens"].numpy()
+    # always include the longest and the shortest request
+    picks = {(int(lens.argmax()), 0), (int(lens.argmin()), Hq - 1)}
+    while len(picks) < min(n, R * Hq):
+        picks.add((int(rng.integers(R)), int(rng.integers(Hq))))
+    return sorted(picks)
+
+
+def test_full_llama3_8b_ctx4096_all_rows():
+    print("generating llama3_8b_ctx4096", flush=True)
+    b = W.generate(W.WORKLOADS["llama3_8b_ctx4096"], threads=16)
+    got, info = gpu_of(b)
+    print("partitioning", info, flush=True)
+    e = check(got, oracle_of(b), "bf16_f32")
+    print("max abs err, lse err", e, flush=True)
+
+
+def test_full_llama3_70b_headshare_paged_all_rows():
+    print("generating llama3_70b_headshare_paged", flush=True)
+    b = W.generate(W.WORKLOADS["llama3_70b_headshare_paged"], threads=16)
+    got, info = gpu_of(b, max_seq_len=32768)
+    print("partitioning", info, flush=True)
+    e = check(got, oracle_of(b), "bf16_f32")
+    print("max abs err, lse err", e, flush=True)
+
+
+def test_full_longctx_split64_sampled_rows():
+    print("generating longctx_split64 (8 GiB)", flush=True)
+    b = W.generate(W.WORKLOADS["longctx_split64"], threads=16)
+    got, info = gpu_of(b)
+    assert info == (64, 2048)
+    pairs = sample_pairs(b, 48, 4)
+    print("oracle on", len(pairs), "rows", flush=True)
+    e = check(got, oracle_of(b, pairs=pairs), "bf16_f32", pairs=pairs)
+    print("max abs err, lse err", e, flush=True)
+    # properties that hold for every row: finite, inside the value range of N(0,1) data
+    out, lse = got
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    assert np.abs(out).max() < 1.0 and (lse > math.log(131072) - 1).all()
+
+
+def test_full_fp8_paged_sampled_rows():
+    print("generating fp8_paged", flush=True)
+    b = W.generate(W.WORKLOADS["fp8_paged"], threads=16)
+    got, info = gpu_of(b, max_seq_len=16384)
+    print("partitioning", info, flush=True)
+    pairs = sample_pairs(b, 256, 5)
+    e = check(got, oracle_of(b, pairs=pairs), "fp8", pairs=pairs)
+    print("max abs err, lse err", e, flush=True)
+    out, lse = got
+    assert np.isfinite(out).all() and np.isfinite(lse).all()

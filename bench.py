@@ -39,6 +39,17 @@ def main() -> int:
                     help="distinct KV buffers to rotate through (defeats the 256 MB cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--block-size", type=int, default=-1,
+                    help="override the workload's cache layout: 0 contiguous, 16 paged")
+    ap.add_argument("--kv-dtype", default="", choices=["", "bf16", "fp8"],
+                    help="override the workload's cache dtype")
+    ap.add_argument("--fixed-len", type=int, default=0,
+                    help="override the workload's length mix: every context this long")
+    ap.add_argument("--no-events", action="store_true",
+                    help="do not record per-launch events inside the timed region")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="instead of the operator, run a plain device copy of 1 GiB a few times "
+                         "(reference reading for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU; run with --gpus 1 "
@@ -54,7 +65,22 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": src.numel() * 4,
+                          "copy_calibration_bytes_written": src.numel() * 4, "launches": 5}))
+        return 0
     w = W.WORKLOADS[args.workload]
+    if args.block_size >= 0 or args.kv_dtype or args.fixed_len:
+        import dataclasses
+        w = dataclasses.replace(
+            w, block_size=w.block_size if args.block_size < 0 else args.block_size,
+            kv_dtype=args.kv_dtype or w.kv_dtype,
+            len_recipe=("fixed", args.fixed_len) if args.fixed_len else w.len_recipe)
     t_gen = time.time()
     b = W.generate(w, threads=16)
     lens = b["seq_lens"].numpy()
@@ -113,12 +139,15 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        ev[i][0].record()
+        if not args.no_events:
+            ev[i][0].record()
         step(i)
-        ev[i][1].record()
+        if not args.no_events:
+            ev[i][1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    per_call_ms = np.array([a.elapsed_time(bb) for a, bb in ev])
+    per_call_ms = (np.array([a.elapsed_time(bb) for a, bb in ev]) if not args.no_events
+                   else np.full(args.steps, wall * 1e3 / args.steps))
     ms_per_step = wall * 1e3 / args.steps
 
     ab = W.algorithmic_bytes(w, lens, out_bytes=2 if args.out_dtype == "bf16" else 4,

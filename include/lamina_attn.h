@@ -63,7 +63,7 @@ typedef struct {
     int32_t max_batch;      /* upper bound on `batch` of any call; sizes grid and workspace     */
     int32_t max_seq_len;    /* upper bound on any seq_lens[r]; sizes the split-KV partition     */
     int32_t num_splits;     /* 0: library chooses; 1: never split; N>1: exactly N partitions of
-                               ceil(max_seq_len / N) tokens (rounded up to a multiple of 64)    */
+                               ceil(max_seq_len / N) tokens (rounded up to a multiple of 256)    */
     float   softmax_scale;  /* 0 means 1/sqrt(head_dim)                                         */
     int32_t device;         /* HIP device ordinal the handle is bound to                        */
     int32_t kernel;         /* LAMINA_KERNEL_MFMA or LAMINA_KERNEL_VALU                         */

@@ -35,12 +35,14 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
+// Read-only index arrays are read through the constant address space so that uniform reads
+// stay on the scalar unit (and off the in-order vector-memory counter) inside the tile loop.
+typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
 
 constexpr int kHeadDim = 128;
 constexpr int kWaves = 4;              // wavefronts per work-group
 constexpr int kThreads = kWaves * 64;
-constexpr int kTile = 32;              // tokens per wavefront tile (two 16-token MFMA sub-tiles)
-constexpr int kChunkAlign = kWaves * kTile;
+constexpr int kChunkAlign = 256;       // partition sizes are multiples of 4 wavefronts x 64 tokens
 constexpr int kMaxGroup = 16;          // query heads per kv head the MFMA tile can hold
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -134,13 +136,21 @@ __device__ __forceinline__ void store_out(void *out, int out_is_bf16, size_t idx
 template <bool FP8, bool PAGED>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainParams prm)
 {
+    constexpr int TILE = FP8 ? 64 : 32;                   // tokens per wavefront tile (16 KiB of K+V)
+    constexpr int NSUB = TILE / 16;                       // 16-token MFMA sub-tiles per tile
+    constexpr int NPAIR = NSUB / 2;                       // 32-token contraction steps for p.V
     constexpr int ROWB = FP8 ? 128 : 256;                 // bytes of one K or V row
     constexpr int VSTRIDE = ROWB + (FP8 ? 16 : 32);       // LDS row pitch (bank spreading)
-    constexpr int KR = FP8 ? 4 : 8;                       // 128-bit K loads per lane per tile
-    constexpr int VR = FP8 ? 4 : 8;                       // 128-bit V loads per lane per tile
-    constexpr int VBUF = kTile * VSTRIDE;                 // V staging bytes per wavefront
+    constexpr int KR = 8;                                 // 128-bit K loads per lane per tile
+    constexpr int VR = 8;                                 // 128-bit V loads per lane per tile
+    constexpr int KPS = KR / NSUB;                        // K loads per sub-tile
+    constexpr int LPR = ROWB / 16;                        // lanes that cover one V row
+    constexpr int RPI = 64 / LPR;                         // V rows per load instruction
+    constexpr int VBUF = TILE * VSTRIDE;                  // V staging bytes per wavefront
+    constexpr bool SPLIT_P = !FP8;                        // carry p as hi + lo bf16 halves
     constexpr int MERGE_BYTES = kWaves * kMaxGroup * (kHeadDim + 2) * 4;
     constexpr int SMEM = (kWaves * VBUF > MERGE_BYTES) ? kWaves * VBUF : MERGE_BYTES;
+    static_assert(VR * RPI == TILE && KR % NSUB == 0, "tile geometry");
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
 
     const int tid = threadIdx.x;
@@ -171,7 +181,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         return;
     }
     const int t1 = min(len, t0 + prm.chunk);
-    const int last = len - 1;
+    const int last = t1 - 1;                              // loads never go past this token
 
     // ---- Q as MFMA B operand: column = head col, k-step s holds 8 dims --------------------
     bf16x8 qop[4];
@@ -194,11 +204,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
 
     const unsigned char *kbase;
     const unsigned char *vbase;
-    const int32_t *bt_row = nullptr;
+    const_i32_ptr bt_row = nullptr;
     if (PAGED) {
         kbase = prm.k + (long long)g * prm.pool_stride_head_b;
         vbase = prm.v + (long long)g * prm.pool_stride_head_b;
-        bt_row = prm.block_table + (size_t)r * prm.bt_stride;
+        bt_row = (const_i32_ptr)(prm.block_table + (size_t)r * prm.bt_stride);
     } else {
         const long long off = (long long)r * prm.stride_req_b + (long long)g * prm.stride_head_b;
         kbase = prm.k + off;
@@ -207,37 +217,34 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
 
     unsigned char *vbuf = smem + w * VBUF;                // this wavefront's V staging area
 
-    // Issue all loads of the tile starting at token ts.  Tokens at or beyond len are
-    // redirected to the last valid row so that no byte outside the request is touched;
+    // Pool blocks of the 16-token pages of the tile starting at ts (wave-uniform, scalar
+    // loads).  Looked up one tile ahead of the loads that need them.
+    auto fetch_pages = [&](int ts, int(&pg)[NSUB]) {
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub)
+            pg[sub] = PAGED ? bt_row[min(ts + sub * 16, last) >> 4] : 0;
+    };
+
+    // Issue all loads of the tile starting at token ts.  Tokens beyond the partition are
+    // redirected to its last valid row so that no byte outside the request is touched;
     // their scores are masked later.
-    auto issue_loads = [&](int ts, u32x4(&kr)[KR], u32x4(&vr)[VR]) {
-        long long page_off[2] = {0, 0};
-        if (PAGED) {
+    auto issue_loads = [&](int ts, const int(&pg)[NSUB], u32x4(&kr)[KR], u32x4(&vr)[VR]) {
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                const int pg = min(ts + sub * 16, last) >> 4;      // wave-uniform
-                page_off[sub] = (long long)bt_row[pg] * prm.pool_stride_block_b;
-            }
-        }
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
+        for (int sub = 0; sub < NSUB; ++sub) {
             const int tok = min(ts + sub * 16 + col, last);
             const unsigned char *row =
-                PAGED ? kbase + page_off[sub] + (tok & 15) * ROWB
+                PAGED ? kbase + (long long)pg[sub] * prm.pool_stride_block_b + (tok & 15) * ROWB
                       : kbase + (long long)tok * prm.stride_tok_b;
 #pragma unroll
-            for (int s = 0; s < KR / 2; ++s)
-                kr[sub * (KR / 2) + s] = load_stream_128(row + (s * 4 + quad) * 16);
+            for (int s = 0; s < KPS; ++s)
+                kr[sub * KPS + s] = load_stream_128(row + (s * 4 + quad) * 16);
         }
-        constexpr int LPR = ROWB / 16;                    // lanes per V row
-        constexpr int RPI = 64 / LPR;                     // V rows per load instruction
 #pragma unroll
         for (int i = 0; i < VR; ++i) {
-            const int trow = i * RPI + lane / LPR;        // row inside the tile
-            const int tok = min(ts + trow, last);
+            const int tok = min(ts + i * RPI + lane / LPR, last);
             const int sub = (i * RPI) / 16;               // compile-time per instruction
             const unsigned char *row =
-                PAGED ? vbase + page_off[sub] + (tok & 15) * ROWB
+                PAGED ? vbase + (long long)pg[sub] * prm.pool_stride_block_b + (tok & 15) * ROWB
                       : vbase + (long long)tok * prm.stride_tok_b;
             vr[i] = load_stream_128(row + (lane % LPR) * 16);
         }
@@ -252,11 +259,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         o_acc[db] = z;
     }
 
-    auto compute = [&](int ts, const u32x4(&kr)[KR], const u32x4(&vr)[VR]) {
-        // ---- scores: two 16-token sub-tiles ------------------------------------------------
-        f32x4 sc[2];
+    // First half of a tile: everything that reads the tile's load registers.
+    auto consume = [&](const u32x4(&kr)[KR], const u32x4(&vr)[VR], f32x4(&sc)[NSUB]) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
+        for (int sub = 0; sub < NSUB; ++sub) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
             if (FP8) {
 #pragma unroll
@@ -276,44 +282,44 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             }
             sc[sub] = acc;
         }
-        // ---- stage V in LDS (row-major, padded pitch) ----------------------------------------
-        {
-            constexpr int LPR = ROWB / 16;
-            constexpr int RPI = 64 / LPR;
+        // stage V in LDS (row-major, padded pitch)
 #pragma unroll
-            for (int i = 0; i < VR; ++i) {
-                const int trow = i * RPI + lane / LPR;
-                *reinterpret_cast<u32x4 *>(vbuf + trow * VSTRIDE + (lane % LPR) * 16) = vr[i];
-            }
+        for (int i = 0; i < VR; ++i) {
+            const int trow = i * RPI + lane / LPR;
+            *reinterpret_cast<u32x4 *>(vbuf + trow * VSTRIDE + (lane % LPR) * 16) = vr[i];
         }
-        // ---- online softmax in the log2 domain ----------------------------------------------
-        float x[8];
+    };
+
+    // Second half: online softmax in the log2 domain, then O^T += V^T . P^T from LDS.
+    auto finish = [&](int ts, const f32x4(&sc)[NSUB]) {
+        float x[NSUB * 4];
         float tmax = -INFINITY;
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int tok = ts + sub * 16 + quad * 4 + v;
                 float s = sc[sub][v] * c_log2;
-                s = (tok < len) ? s : -INFINITY;
+                s = (tok < t1) ? s : -INFINITY;
                 x[sub * 4 + v] = s;
                 tmax = fmaxf(tmax, s);
             }
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m_run, tmax);           // finite: the tile has a valid token
+        const float m_new = fmaxf(m_run, tmax);           // finite from the first tile on
         const float alpha = fast_exp2(m_run - m_new);     // exp2(-inf) = 0 on the first tile
         m_run = m_new;
         float psum = 0.0f;
-        bf16x8 p_hi, p_lo;
+        bf16x8 p_hi[NPAIR], p_lo[NPAIR];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < NSUB * 4; ++j) {
             const float pj = fast_exp2(x[j] - m_new);
             psum += pj;
             // p = hi + lo with both halves bf16: keeps ~16 significant bits through the MFMA
             const __bf16 h = static_cast<__bf16>(pj);
-            p_hi[j] = h;
-            p_lo[j] = static_cast<__bf16>(pj - static_cast<float>(h));
+            p_hi[j >> 3][j & 7] = h;
+            if (SPLIT_P)
+                p_lo[j >> 3][j & 7] = static_cast<__bf16>(pj - static_cast<float>(h));
         }
         l_run = l_run * alpha + psum;
         if (__any(alpha != 1.0f)) {
@@ -321,57 +327,78 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             for (int db = 0; db < 8; ++db)
                 o_acc[db] *= alpha;
         }
-        // ---- O^T += V^T . P^T -----------------------------------------------------------------
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
-            bf16x8 vop;
-            if (FP8) {
-                // 8 rows x 16 byte-columns per 16-lane block; lane supplies row col/2
-                const int rr = col >> 1;
-                const int trow = (rr < 4) ? (quad * 4 + rr) : (16 + quad * 4 + rr - 4);
-                const unsigned char *a = vbuf + trow * VSTRIDE + db * 16 + (col & 1) * 8;
-                const i32x2 raw = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-                    (i32x2 __attribute__((address_space(3))) *)(a));
-                vop = join_bf16x4(fp8x4_to_bf16((unsigned)raw[0]), fp8x4_to_bf16((unsigned)raw[1]));
-            } else {
-                // 4 rows x 16 columns per 16-lane block; lane supplies row col/4, 4 columns
-                const unsigned char *a =
-                    vbuf + (quad * 4 + (col >> 2)) * VSTRIDE + db * 32 + (col & 3) * 8;
-                const s16x4 ra = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (s16x4 __attribute__((address_space(3))) *)(a));
-                const s16x4 rb = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (s16x4 __attribute__((address_space(3))) *)(a + 16 * VSTRIDE));
-                vop = join_bf16x4(__builtin_bit_cast(bf16x4, ra), __builtin_bit_cast(bf16x4, rb));
+#pragma unroll
+            for (int pp = 0; pp < NPAIR; ++pp) {
+                bf16x8 vop;
+                if (FP8) {
+                    // 8 rows x 16 byte-columns per 16-lane block; lane supplies row col/2
+                    const int rr = col >> 1;
+                    const int trow =
+                        pp * 32 + ((rr < 4) ? (quad * 4 + rr) : (16 + quad * 4 + rr - 4));
+                    const unsigned char *a = vbuf + trow * VSTRIDE + db * 16 + (col & 1) * 8;
+                    const i32x2 raw = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                        (i32x2 __attribute__((address_space(3))) *)(a));
+                    vop = join_bf16x4(fp8x4_to_bf16((unsigned)raw[0]),
+                                      fp8x4_to_bf16((unsigned)raw[1]));
+                } else {
+                    // 4 rows x 16 columns per 16-lane block; lane supplies row col/4, 4 columns
+                    const unsigned char *a = vbuf + (pp * 32 + quad * 4 + (col >> 2)) * VSTRIDE +
+                                             db * 32 + (col & 3) * 8;
+                    const s16x4 ra = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3))) *)(a));
+                    const s16x4 rb = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3))) *)(a + 16 * VSTRIDE));
+                    vop = join_bf16x4(__builtin_bit_cast(bf16x4, ra),
+                                      __builtin_bit_cast(bf16x4, rb));
+                }
+                o_acc[db] =
+                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_hi[pp], o_acc[db], 0, 0, 0);
+                if (SPLIT_P)
+                    o_acc[db] =
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_lo[pp], o_acc[db], 0, 0, 0);
             }
-            o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_hi, o_acc[db], 0, 0, 0);
-            o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_lo, o_acc[db], 0, 0, 0);
         }
     };
 
-    // ---- stream this wavefront's tiles, loads one tile ahead of the arithmetic --------------
+    // ---- stream this wavefront's tiles --------------------------------------------------------
+    // Tiles w, w+4, w+8, ... of the partition.  Two register sets (A, B) alternate; a set is
+    // refilled with the tile two steps ahead as soon as its registers have been read, so one
+    // to two tiles (16-32 KiB per wavefront) are always in flight.  The loop body is a single
+    // basic block: a wavefront with an odd tile count runs one fully masked tile, and the
+    // refills past the end are redirected to the last valid row.
     {
-        u32x4 kA[KR], vA[VR], kB[KR], vB[VR];
-        constexpr int step = kWaves * kTile;
-        int ts = t0 + w * kTile;
+        constexpr int step = kWaves * TILE;
+        int ts = t0 + w * TILE;
         if (ts < t1) {
-            issue_loads(ts, kA, vA);
-            for (;;) {
-                int tn = ts + step;
-                if (tn >= t1) {
-                    compute(ts, kA, vA);
-                    break;
-                }
-                issue_loads(tn, kB, vB);
-                compute(ts, kA, vA);
-                ts = tn;
-                tn = ts + step;
-                if (tn >= t1) {
-                    compute(ts, kB, vB);
-                    break;
-                }
-                issue_loads(tn, kA, vA);
-                compute(ts, kB, vB);
-                ts = tn;
+            const int ntiles = (t1 - ts + step - 1) / step;
+            u32x4 kA[KR], vA[VR], kB[KR], vB[VR];
+            int pg[NSUB];
+            f32x4 sc[NSUB];
+            fetch_pages(ts, pg);
+            issue_loads(ts, pg, kA, vA);
+            __builtin_amdgcn_sched_barrier(0);            // A must be the older set
+            fetch_pages(ts + step, pg);
+            issue_loads(ts + step, pg, kB, vB);
+            fetch_pages(ts + 2 * step, pg);
+            __builtin_amdgcn_sched_barrier(0);
+            for (int it = 0; it < ntiles; it += 2) {
+                consume(kA, vA, sc);
+                __builtin_amdgcn_sched_barrier(0);
+                issue_loads(ts + 2 * step, pg, kA, vA);
+                fetch_pages(ts + 3 * step, pg);
+                __builtin_amdgcn_sched_barrier(0);
+                finish(ts, sc);
+                __builtin_amdgcn_sched_barrier(0);
+                consume(kB, vB, sc);
+                __builtin_amdgcn_sched_barrier(0);
+                issue_loads(ts + 3 * step, pg, kB, vB);
+                fetch_pages(ts + 4 * step, pg);
+                __builtin_amdgcn_sched_barrier(0);
+                finish(ts + step, sc);
+                __builtin_amdgcn_sched_barrier(0);
+                ts += 2 * step;
             }
         }
     }

@@ -151,11 +151,11 @@ def test_fp8_contiguous():
 
 
 def test_split_kv_64_partitions_including_requests_shorter_than_the_split_count():
-    # 64 partitions of 128 tokens over max_seq_len 8192; several requests leave most empty
-    lens = [8192, 1, 127, 128, 129, 5000, 64, 8191]
+    # 64 partitions of 256 tokens over max_seq_len 16384; several requests leave most empty
+    lens = [16384, 1, 255, 256, 257, 5000, 64, 16383]
     b = sized("longctx_split64", lens)
     got, info = gpu_of(b)
-    assert info == (64, 128)
+    assert info == (64, 256)
     check(got, oracle_of(b), "bf16_f32")
 
 

@@ -44,6 +44,8 @@ constexpr int kWaves = 4;              // wavefronts per work-group
 constexpr int kThreads = kWaves * 64;
 constexpr int kChunkAlign = 256;       // partition sizes are multiples of 4 wavefronts x 64 tokens
 constexpr int kMaxGroup = 16;          // query heads per kv head the MFMA tile can hold
+constexpr int kMaxSplitBatch = 2048;   // requests per call when the KV range is partitioned
+constexpr int kTableSlots = 256;       // work items one work-group can be dealt per call
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -64,6 +66,7 @@ struct MainParams {
     int bt_stride;
     int Hq, Hkv, G;
     int P, chunk;
+    int batch;
     int out_is_bf16;
     float scale_log2;                  // softmax scale times log2(e)
 };
@@ -118,9 +121,28 @@ __device__ __forceinline__ void store_out(void *out, int out_is_bf16, size_t idx
 }
 
 // -------------------------------------------------------------------------------------------
-// Main pass.  Grid: batch * Hkv * P work-groups of 256 threads; work-group id decodes to
-// (request r, kv head g, partition p), p fastest.  Partition p owns tokens
-// [p*chunk, min((p+1)*chunk, seq_lens[r])); a work-group whose range is empty exits at once.
+// Main pass: a persistent kernel.  The grid is a fixed number of work-groups (two per compute
+// unit) that stay resident and share out a compact list of work items.
+//
+// Work items.  Request r is cut into n(r) = max(1, ceil(seq_lens[r] / chunk)) partitions of
+// `chunk` tokens (one partition when the handle is unsplit); an item is (partition, kv head).
+// Items are numbered with the kv head fastest and requests in order, skipping nothing but
+// the partitions a request is too short to have; work-group j takes items j, j + grid,
+// j + 2 grid, ...  Every work-group derives the numbering itself from seq_lens (a prefix sum
+// and a table of its own items in LDS), so the host never reads seq_lens and no planning
+// kernel runs.  Equal-sized items dealt round-robin keep skewed batches balanced.
+//
+// Inside an item the four wavefronts take 32-token (bf16) or 64-token (fp8) tiles
+// w, w+4, w+8, ... and never synchronise until the item ends, where they combine their
+// (max, denominator, output) triples through LDS -- the same identity as the cross-partition
+// merge.  A request with a single partition is written straight to out/lse; otherwise the
+// item writes the partial pair (A_q(I), ln S_q(I)) of Sec. 4.2.2 to the workspace.
+//
+// Streaming.  Each wavefront keeps two register sets of 16 KiB of K+V in flight and refills a
+// set as soon as its registers have been read.  When an item runs out of tiles the refills
+// continue with the first two tiles of the wavefront's NEXT item, so the memory pipeline
+// never drains at an item boundary; the steady-state loop body is one basic block (which set
+// of addresses a refill uses is a scalar select, not a branch).
 //
 // Lane roles inside a wavefront (col = lane % 16, quad = lane / 16):
 //   scores   S^T[token][head] = K[token][:] . Q[head][:]  -- MFMA A = K sub-tile (row = token
@@ -148,10 +170,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     constexpr int RPI = 64 / LPR;                         // V rows per load instruction
     constexpr int VBUF = TILE * VSTRIDE;                  // V staging bytes per wavefront
     constexpr bool SPLIT_P = !FP8;                        // carry p as hi + lo bf16 halves
-    constexpr int MERGE_BYTES = kWaves * kMaxGroup * (kHeadDim + 2) * 4;
-    constexpr int SMEM = (kWaves * VBUF > MERGE_BYTES) ? kWaves * VBUF : MERGE_BYTES;
+    constexpr int step = kWaves * TILE;                   // token stride between a wave's tiles
+    // A wavefront's share of the end-of-item combine lives inside its own V staging area.
+    static_assert(kMaxGroup * (kHeadDim + 2) * 4 <= VBUF, "combine area must fit the staging");
     static_assert(VR * RPI == TILE && KR % NSUB == 0, "tile geometry");
-    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kWaves * VBUF];
+    __shared__ int s_cum[kMaxSplitBatch + 1];             // partitions before request r
+    __shared__ int s_tab_r[kTableSlots];                  // this work-group's items: request
+    __shared__ int s_tab_c[kTableSlots];                  //                          partition
+    __shared__ int s_wsum[kWaves];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -159,76 +186,147 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     const int col = lane & 15;
     const int quad = lane >> 4;
     const int G = prm.G;
+    const int R = prm.batch;
+    const int C = prm.chunk;
+    const int Hkv = prm.Hkv;
+    const bool split = prm.P > 1;
+    const int j = blockIdx.x;
+    const int nwg = gridDim.x;
+    const const_i32_ptr lens = (const_i32_ptr)prm.seq_lens;
 
-    int id = blockIdx.x;
-    const int p = id % prm.P;
-    id /= prm.P;
-    const int g = id % prm.Hkv;
-    const int r = id / prm.Hkv;
-    const int len = prm.seq_lens[r];
-    const int t0 = p * prm.chunk;
-    const int hq0 = g * G;                                // first query head of this group
+    auto nparts = [&](int len) { return min(prm.P, max(1, (len + C - 1) / C)); };
 
-    if (t0 >= len) {
-        // Empty partition.  Unsplit and an empty context: the result is defined as 0 / -inf.
-        if (prm.P == 1) {
-            for (int i = tid; i < G * kHeadDim; i += kThreads)
-                store_out(prm.out, prm.out_is_bf16,
-                          ((size_t)r * prm.Hq + hq0) * kHeadDim + i, 0.0f);
-            if (prm.lse && tid < G)
-                prm.lse[(size_t)r * prm.Hq + hq0 + tid] = -INFINITY;
-        }
-        return;
-    }
-    const int t1 = min(len, t0 + prm.chunk);
-    const int last = t1 - 1;                              // loads never go past this token
-
-    // ---- Q as MFMA B operand: column = head col, k-step s holds 8 dims --------------------
-    bf16x8 qop[4];
-    {
-        const __bf16 *qrow =
-            static_cast<const __bf16 *>(prm.q) + ((size_t)r * prm.Hq + hq0 + col) * kHeadDim;
+    // ---- the work list ---------------------------------------------------------------------
+    int total_items;
+    if (split) {
+        const int per = (R + kThreads - 1) / kThreads;
+        const int b = tid * per;
+        const int e = min(R, b + per);
+        int sum = 0;
+        for (int i = b; i < e; ++i)
+            sum += nparts(prm.seq_lens[i]);
+        int inc = sum;                                    // inclusive scan inside the wavefront
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            // The dims a lane holds in step s must be the dims its K register holds there.
-            const int chunk8 = FP8 ? (((s >> 1) * 4 + quad) * 2 + (s & 1)) : (s * 4 + quad);
-            bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-            qop[s] = z;
-            if (col < G)
-                qop[s] = *reinterpret_cast<const bf16x8 *>(qrow + chunk8 * 8);
+        for (int off = 1; off < 64; off <<= 1) {
+            const int t = __shfl_up(inc, off);
+            if (lane >= off)
+                inc += t;
         }
-    }
-    float c_log2 = prm.scale_log2;
-    if (FP8)
-        c_log2 *= prm.k_scale[(size_t)r * prm.Hkv + g];   // K scale folds into the score scale
-
-    const unsigned char *kbase;
-    const unsigned char *vbase;
-    const_i32_ptr bt_row = nullptr;
-    if (PAGED) {
-        kbase = prm.k + (long long)g * prm.pool_stride_head_b;
-        vbase = prm.v + (long long)g * prm.pool_stride_head_b;
-        bt_row = (const_i32_ptr)(prm.block_table + (size_t)r * prm.bt_stride);
+        if (lane == 63)
+            s_wsum[w] = inc;
+        __syncthreads();
+        int wbase = 0, tot = 0;
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww) {
+            const int v = s_wsum[ww];
+            wbase += (ww < w) ? v : 0;
+            tot += v;
+        }
+        int run = wbase + inc - sum;
+        for (int i = b; i < e; ++i) {
+            s_cum[i] = run;
+            run += nparts(prm.seq_lens[i]);
+        }
+        if (tid == 0)
+            s_cum[R] = tot;
+        __syncthreads();
+        total_items = __builtin_amdgcn_readfirstlane(tot) * Hkv;
     } else {
-        const long long off = (long long)r * prm.stride_req_b + (long long)g * prm.stride_head_b;
-        kbase = prm.k + off;
-        vbase = prm.v + off;
+        total_items = R * Hkv;
     }
+    const int nslots = (j < total_items) ? (total_items - j + nwg - 1) / nwg : 0;
+    if (nslots == 0)
+        return;
+    if (split) {
+        for (int sl = tid; sl < nslots; sl += kThreads) {  // nslots <= kTableSlots (host check)
+            const int cidx = (j + sl * nwg) / Hkv;
+            int lo = 0, hi = R;                           // largest r with cum[r] <= cidx
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (s_cum[mid] <= cidx)
+                    lo = mid;
+                else
+                    hi = mid;
+            }
+            s_tab_r[sl] = lo;
+            s_tab_c[sl] = cidx - s_cum[lo];
+        }
+        __syncthreads();
+    }
+
+    // Wave-uniform description of the tiles one wavefront owns in one item.
+    struct Desc {
+        int slot;                     // -1: none
+        int r, g;
+        int t0w;                      // first token of this wavefront's first tile
+        int t1;                       // end of the item's token range
+        int n_even;                   // tile slots this wavefront runs here (tiles rounded up to even)
+        const unsigned char *kbase;
+        const unsigned char *vbase;
+        const_i32_ptr bt;
+    };
+    auto identify = [&](int slot, int &r, int &g, int &c) {
+        const int it = j + slot * nwg;
+        g = it % Hkv;
+        if (split) {
+            r = __builtin_amdgcn_readfirstlane(s_tab_r[slot]);
+            c = __builtin_amdgcn_readfirstlane(s_tab_c[slot]);
+        } else {
+            r = it / Hkv;
+            c = 0;
+        }
+    };
+    auto describe = [&](int slot, Desc &d) {
+        int r, g, c;
+        identify(slot, r, g, c);
+        const int len = lens[r];
+        d.slot = slot;
+        d.r = r;
+        d.g = g;
+        d.t0w = c * C + w * TILE;
+        d.t1 = min(len, c * C + C);
+        const int nt = (d.t0w < d.t1) ? (d.t1 - d.t0w + step - 1) / step : 0;
+        d.n_even = (nt + 1) & ~1;
+        if (PAGED) {
+            d.kbase = prm.k + (long long)g * prm.pool_stride_head_b;
+            d.vbase = prm.v + (long long)g * prm.pool_stride_head_b;
+            d.bt = (const_i32_ptr)(prm.block_table + (size_t)r * prm.bt_stride);
+        } else {
+            const long long off =
+                (long long)r * prm.stride_req_b + (long long)g * prm.stride_head_b;
+            d.kbase = prm.k + off;
+            d.vbase = prm.v + off;
+            d.bt = nullptr;
+        }
+    };
+    // First item at or after `from` in which this wavefront has at least one tile.
+    auto find_next = [&](int from, Desc &d) {
+        d.slot = -1;
+        for (int sl = from; sl < nslots; ++sl) {
+            Desc t;
+            describe(sl, t);
+            if (t.n_even > 0) {
+                d = t;
+                return;
+            }
+        }
+    };
 
     unsigned char *vbuf = smem + w * VBUF;                // this wavefront's V staging area
 
-    // Pool blocks of the 16-token pages of the tile starting at ts (wave-uniform, scalar
-    // loads).  Looked up one tile ahead of the loads that need them.
-    auto fetch_pages = [&](int ts, int(&pg)[NSUB]) {
+    // Pool blocks of the 16-token pages of the tile starting at ts (wave-uniform scalar
+    // loads), looked up one refill ahead of the loads that need them.
+    auto fetch_pages = [&](const_i32_ptr bt, int ts, int last, int(&pg)[NSUB]) {
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub)
-            pg[sub] = PAGED ? bt_row[min(ts + sub * 16, last) >> 4] : 0;
+            pg[sub] = PAGED ? bt[min(ts + sub * 16, last) >> 4] : 0;
     };
 
-    // Issue all loads of the tile starting at token ts.  Tokens beyond the partition are
-    // redirected to its last valid row so that no byte outside the request is touched;
-    // their scores are masked later.
-    auto issue_loads = [&](int ts, const int(&pg)[NSUB], u32x4(&kr)[KR], u32x4(&vr)[VR]) {
+    // Issue all loads of the tile starting at token ts.  Tokens beyond `last` (the item's
+    // last valid token) are redirected to that row, so no byte outside the request is
+    // touched; their scores are masked later.
+    auto issue_loads = [&](const unsigned char *kbase, const unsigned char *vbase, int ts,
+                           int last, const int(&pg)[NSUB], u32x4(&kr)[KR], u32x4(&vr)[VR]) {
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub) {
             const int tok = min(ts + sub * 16 + col, last);
@@ -250,6 +348,28 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         }
     };
 
+    // Q as MFMA B operand: column = head col, k-step s holds 8 dims.
+    bf16x8 qop[4];
+    auto load_q = [&](int r, int g) {
+        const __bf16 *qrow =
+            static_cast<const __bf16 *>(prm.q) + ((size_t)r * prm.Hq + g * G + col) * kHeadDim;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            // The dims a lane holds in step s must be the dims its K register holds there.
+            const int chunk8 = FP8 ? (((s >> 1) * 4 + quad) * 2 + (s & 1)) : (s * 4 + quad);
+            bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+            qop[s] = z;
+            if (col < G)
+                qop[s] = *reinterpret_cast<const bf16x8 *>(qrow + chunk8 * 8);
+        }
+    };
+    auto score_scale = [&](int r, int g) {
+        float c = prm.scale_log2;
+        if (FP8)                                          // K scale folds into the score scale
+            c *= ((const __attribute__((address_space(4))) float *)prm.k_scale)[(size_t)r * Hkv + g];
+        return c;
+    };
+
     float m_run = -INFINITY;        // running max of log2-domain scores, head = col
     float l_run = 0.0f;             // this lane's share of the running denominator
     f32x4 o_acc[8];                 // O^T[dim = db*16 + quad*4 + v][head = col]
@@ -258,6 +378,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         f32x4 z = {0.f, 0.f, 0.f, 0.f};
         o_acc[db] = z;
     }
+    float c_log2 = 0.0f;
+    int cur_t1 = 0;
 
     // First half of a tile: everything that reads the tile's load registers.
     auto consume = [&](const u32x4(&kr)[KR], const u32x4(&vr)[VR], f32x4(&sc)[NSUB]) {
@@ -300,7 +422,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             for (int v = 0; v < 4; ++v) {
                 const int tok = ts + sub * 16 + quad * 4 + v;
                 float s = sc[sub][v] * c_log2;
-                s = (tok < t1) ? s : -INFINITY;
+                s = (tok < cur_t1) ? s : -INFINITY;
                 x[sub * 4 + v] = s;
                 tmax = fmaxf(tmax, s);
             }
@@ -312,14 +434,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         float psum = 0.0f;
         bf16x8 p_hi[NPAIR], p_lo[NPAIR];
 #pragma unroll
-        for (int j = 0; j < NSUB * 4; ++j) {
-            const float pj = fast_exp2(x[j] - m_new);
+        for (int jj = 0; jj < NSUB * 4; ++jj) {
+            const float pj = fast_exp2(x[jj] - m_new);
             psum += pj;
             // p = hi + lo with both halves bf16: keeps ~16 significant bits through the MFMA
             const __bf16 h = static_cast<__bf16>(pj);
-            p_hi[j >> 3][j & 7] = h;
+            p_hi[jj >> 3][jj & 7] = h;
             if (SPLIT_P)
-                p_lo[j >> 3][j & 7] = static_cast<__bf16>(pj - static_cast<float>(h));
+                p_lo[jj >> 3][jj & 7] = static_cast<__bf16>(pj - static_cast<float>(h));
         }
         l_run = l_run * alpha + psum;
         if (__any(alpha != 1.0f)) {
@@ -362,92 +484,150 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         }
     };
 
-    // ---- stream this wavefront's tiles --------------------------------------------------------
-    // Tiles w, w+4, w+8, ... of the partition.  Two register sets (A, B) alternate; a set is
-    // refilled with the tile two steps ahead as soon as its registers have been read, so one
-    // to two tiles (16-32 KiB per wavefront) are always in flight.  The loop body is a single
-    // basic block: a wavefront with an odd tile count runs one fully masked tile, and the
-    // refills past the end are redirected to the last valid row.
-    {
-        constexpr int step = kWaves * TILE;
-        int ts = t0 + w * TILE;
-        if (ts < t1) {
-            const int ntiles = (t1 - ts + step - 1) / step;
-            u32x4 kA[KR], vA[VR], kB[KR], vB[VR];
-            int pg[NSUB];
-            f32x4 sc[NSUB];
-            fetch_pages(ts, pg);
-            issue_loads(ts, pg, kA, vA);
-            __builtin_amdgcn_sched_barrier(0);            // A must be the older set
-            fetch_pages(ts + step, pg);
-            issue_loads(ts + step, pg, kB, vB);
-            fetch_pages(ts + 2 * step, pg);
-            __builtin_amdgcn_sched_barrier(0);
-            for (int it = 0; it < ntiles; it += 2) {
+    // End of an item: the four wavefronts combine their triples (same identity as the
+    // cross-partition merge) and the work-group writes the item's result.
+    auto finalize = [&](int slot) {
+        int r, g, c;
+        identify(slot, r, g, c);
+        l_run += __shfl_xor(l_run, 16);
+        l_run += __shfl_xor(l_run, 32);
+        float *mo = reinterpret_cast<float *>(vbuf);      // [kMaxGroup][128] of this wavefront
+        float *mm = mo + kMaxGroup * kHeadDim;            // [kMaxGroup] running max
+        float *ml = mm + kMaxGroup;                       // [kMaxGroup] denominators
+        if (col < G) {
+#pragma unroll
+            for (int db = 0; db < 8; ++db)
+                *reinterpret_cast<f32x4 *>(mo + col * kHeadDim + db * 16 + quad * 4) = o_acc[db];
+            if (quad == 0) {
+                mm[col] = m_run;
+                ml[col] = l_run;
+            }
+        }
+        m_run = -INFINITY;
+        l_run = 0.0f;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+            f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            o_acc[db] = z;
+        }
+        __syncthreads();
+        const int len = lens[r];
+        const bool whole = nparts(len) == 1;              // the request has no other partition
+        float vs = 1.0f;
+        if (FP8)
+            vs = ((const __attribute__((address_space(4))) float *)prm.v_scale)[(size_t)r * Hkv + g];
+        for (int i = tid; i < G * kHeadDim; i += kThreads) {
+            const int h = i >> 7;
+            const int d = i & 127;
+            float M = -INFINITY;
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww)
+                M = fmaxf(M, reinterpret_cast<const float *>(smem + ww * VBUF)[kMaxGroup * kHeadDim + h]);
+            float L = 0.0f, o = 0.0f;
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww) {
+                const float *wo = reinterpret_cast<const float *>(smem + ww * VBUF);
+                const float mw = wo[kMaxGroup * kHeadDim + h];
+                const float e = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);   // idle wavefront
+                L += e * wo[kMaxGroup * kHeadDim + kMaxGroup + h];
+                o += e * wo[h * kHeadDim + d];
+            }
+            const bool empty = !(L > 0.0f);               // a request with no tokens at all
+            o = empty ? 0.0f : o / L * vs;
+            const float lse_nat = empty ? -INFINITY : (M + log2f(L)) * kLn2;
+            const size_t row = (size_t)r * prm.Hq + g * G + h;
+            if (whole) {
+                store_out(prm.out, prm.out_is_bf16, row * kHeadDim + d, o);
+                if (d == 0 && prm.lse)
+                    prm.lse[row] = lse_nat;
+            } else {
+                prm.part_out[(row * prm.P + c) * kHeadDim + d] = o;
+                if (d == 0)
+                    prm.part_lse[row * prm.P + c] = lse_nat;
+            }
+        }
+        __syncthreads();                                  // staging may be overwritten again
+    };
+
+    // ---- stream -----------------------------------------------------------------------------
+    u32x4 kA[KR], vA[VR], kB[KR], vB[VR];
+    int pg[NSUB];
+    f32x4 sc[NSUB];
+    Desc nxt;
+    find_next(0, nxt);
+    if (nxt.slot >= 0) {
+        // prologue: the first two tile slots of this wavefront's first item
+        fetch_pages(nxt.bt, nxt.t0w, nxt.t1 - 1, pg);
+        issue_loads(nxt.kbase, nxt.vbase, nxt.t0w, nxt.t1 - 1, pg, kA, vA);
+        __builtin_amdgcn_sched_barrier(0);                // A must be the older set
+        fetch_pages(nxt.bt, nxt.t0w + step, nxt.t1 - 1, pg);
+        issue_loads(nxt.kbase, nxt.vbase, nxt.t0w + step, nxt.t1 - 1, pg, kB, vB);
+        __builtin_amdgcn_sched_barrier(0);
+        load_q(nxt.r, nxt.g);
+        c_log2 = score_scale(nxt.r, nxt.g);
+    }
+    for (int slot = 0; slot < nslots; ++slot) {
+        if (nxt.slot == slot) {
+            // Sets A and B already hold (or are receiving) this item's first two tile slots.
+            const Desc cur = nxt;
+            cur_t1 = cur.t1;
+            find_next(slot + 1, nxt);
+            // Where refills go once this item's tiles are exhausted: the next item's first
+            // two slots, or -- at the very end -- harmless reloads of this item's last row.
+            const bool more = nxt.slot >= 0;
+            const unsigned char *n_kbase = more ? nxt.kbase : cur.kbase;
+            const unsigned char *n_vbase = more ? nxt.vbase : cur.vbase;
+            const const_i32_ptr n_bt = more ? nxt.bt : cur.bt;
+            const int n_t0w = more ? nxt.t0w : cur.t1;
+            const int n_last = (more ? nxt.t1 : cur.t1) - 1;
+            const int c_last = cur.t1 - 1;
+            const int n_even = cur.n_even;
+            // refill number idx (2, 3, ...) of this item -> its addressing, by scalar selects
+            auto target = [&](int idx, const unsigned char *&kb, const unsigned char *&vb,
+                              const_i32_ptr &bt, int &ts, int &last) {
+                const bool in_item = idx < n_even;
+                kb = in_item ? cur.kbase : n_kbase;
+                vb = in_item ? cur.vbase : n_vbase;
+                bt = in_item ? cur.bt : n_bt;
+                ts = in_item ? cur.t0w + idx * step : n_t0w + (idx - n_even) * step;
+                last = in_item ? c_last : n_last;
+            };
+            const unsigned char *kb, *vb;
+            const_i32_ptr bt;
+            int rts, rlast;
+            target(2, kb, vb, bt, rts, rlast);
+            fetch_pages(bt, rts, rlast, pg);
+            int ts = cur.t0w;
+            // Everything issued so far (this item's first two tiles and its Q, all requested
+            // while the previous item was being finished) is waited for here, so that inside
+            // the loop the only vector-memory operations ever outstanding are the refills.
+            __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0), other counters untouched
+            for (int k = 0; k < n_even; k += 2) {
                 consume(kA, vA, sc);
                 __builtin_amdgcn_sched_barrier(0);
-                issue_loads(ts + 2 * step, pg, kA, vA);
-                fetch_pages(ts + 3 * step, pg);
+                target(k + 2, kb, vb, bt, rts, rlast);
+                issue_loads(kb, vb, rts, rlast, pg, kA, vA);
+                target(k + 3, kb, vb, bt, rts, rlast);
+                fetch_pages(bt, rts, rlast, pg);
                 __builtin_amdgcn_sched_barrier(0);
                 finish(ts, sc);
                 __builtin_amdgcn_sched_barrier(0);
                 consume(kB, vB, sc);
                 __builtin_amdgcn_sched_barrier(0);
-                issue_loads(ts + 3 * step, pg, kB, vB);
-                fetch_pages(ts + 4 * step, pg);
+                issue_loads(kb, vb, rts, rlast, pg, kB, vB);
+                target(k + 4, kb, vb, bt, rts, rlast);
+                fetch_pages(bt, rts, rlast, pg);
                 __builtin_amdgcn_sched_barrier(0);
                 finish(ts + step, sc);
                 __builtin_amdgcn_sched_barrier(0);
                 ts += 2 * step;
             }
+            if (more) {
+                load_q(nxt.r, nxt.g);                     // lands while the item is combined
+                c_log2 = score_scale(nxt.r, nxt.g);
+            }
         }
-    }
-
-    // ---- combine the four wavefronts (same identity as the cross-partition merge) -----------
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-    __syncthreads();                                      // everyone is done with V staging
-    float *mo = reinterpret_cast<float *>(smem);          // [kWaves][kMaxGroup][128]
-    float *mm = mo + kWaves * kMaxGroup * kHeadDim;       // [kWaves][kMaxGroup] running max
-    float *ml = mm + kWaves * kMaxGroup;                  // [kWaves][kMaxGroup] denominators
-    if (col < G) {
-#pragma unroll
-        for (int db = 0; db < 8; ++db)
-            *reinterpret_cast<f32x4 *>(mo + ((w * kMaxGroup + col) * kHeadDim) + db * 16 +
-                                       quad * 4) = o_acc[db];
-        if (quad == 0) {
-            mm[w * kMaxGroup + col] = m_run;
-            ml[w * kMaxGroup + col] = l_run;
-        }
-    }
-    __syncthreads();
-    const float vs = FP8 ? prm.v_scale[(size_t)r * prm.Hkv + g] : 1.0f;
-    for (int i = tid; i < G * kHeadDim; i += kThreads) {
-        const int h = i >> 7;
-        const int d = i & 127;
-        float M = -INFINITY;
-#pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww)
-            M = fmaxf(M, mm[ww * kMaxGroup + h]);
-        float L = 0.0f, o = 0.0f;
-#pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww) {
-            const float e = fast_exp2(mm[ww * kMaxGroup + h] - M);   // idle wavefront: 0
-            L += e * ml[ww * kMaxGroup + h];
-            o += e * mo[(ww * kMaxGroup + h) * kHeadDim + d];
-        }
-        o = o / L * vs;
-        const size_t row = (size_t)r * prm.Hq + hq0 + h;
-        const float lse_nat = (M + log2f(L)) * kLn2;
-        if (prm.P == 1) {
-            store_out(prm.out, prm.out_is_bf16, row * kHeadDim + d, o);
-            if (d == 0 && prm.lse)
-                prm.lse[row] = lse_nat;
-        } else {
-            prm.part_out[(row * prm.P + p) * kHeadDim + d] = o;
-            if (d == 0)
-                prm.part_lse[row * prm.P + p] = lse_nat;
-        }
+        finalize(slot);
     }
 }
 
@@ -455,7 +635,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
 // Cross-partition merge (Sec. 4.2.2 identity, P parts, log-sum-exp form):
 //   lse = ln sum_p e^{lse_p},  out = sum_p e^{lse_p - lse} out_p.
 // One work-group of 128 threads per (request, query head); thread d owns output column d.
-// Only the first ceil(len / chunk) partitions were written by the main pass.
+// Only the first ceil(len / chunk) partitions were written by the main pass, and a request
+// with a single partition was already written to out/lse by the main pass.
 // -------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kHeadDim) void merge_partials_kernel(const MergeParams prm)
 {
@@ -463,7 +644,9 @@ __global__ __launch_bounds__(kHeadDim) void merge_partials_kernel(const MergePar
     const int r = row / prm.Hq;
     const int d = threadIdx.x;
     const int len = prm.seq_lens[r];
-    const int np = min(prm.P, (len + prm.chunk - 1) / prm.chunk);
+    const int np = min(prm.P, max(1, (len + prm.chunk - 1) / prm.chunk));
+    if (np == 1)
+        return;                                           // the main pass wrote this row itself
     const float *pl = prm.part_lse + (size_t)row * prm.P;
     const float *po = prm.part_out + (size_t)row * prm.P * kHeadDim;
     float M = -INFINITY;
@@ -475,10 +658,9 @@ __global__ __launch_bounds__(kHeadDim) void merge_partials_kernel(const MergePar
         W += e;
         o += e * po[(size_t)p * kHeadDim + d];
     }
-    const bool empty = (np == 0);
-    store_out(prm.out, prm.out_is_bf16, (size_t)row * kHeadDim + d, empty ? 0.0f : o / W);
+    store_out(prm.out, prm.out_is_bf16, (size_t)row * kHeadDim + d, o / W);
     if (d == 0 && prm.lse)
-        prm.lse[row] = empty ? -INFINITY : M + logf(W);
+        prm.lse[row] = M + logf(W);
 }
 
 }  // namespace
@@ -494,6 +676,7 @@ struct lamina_attn {
     float scale;
     float *workspace;            // part_out followed by part_lse; nullptr when unsplit
     size_t workspace_bytes;
+    int resident_wgs;            // persistent grid: two work-groups per compute unit
     char err[256];
 };
 
@@ -508,23 +691,32 @@ struct Plan {
     int split_tokens;
 };
 
-// Partitioning.  Explicit num_splits is honoured; otherwise partitions of about 1024 tokens
-// (512 when that still leaves the chip short of work-groups), unsplit when one covers it all.
+// Most work items any call may produce: every resident work-group keeps a table of at most
+// kTableSlots items, and the grid has at least kMinGrid work-groups.
+constexpr long long kMinGrid = 256;
+constexpr long long kMaxItems = kTableSlots * kMinGrid;
+
+// Partitioning.  Explicit num_splits is honoured.  Otherwise: batches that already hold one
+// item per resident work-group with contexts of at most 4096 tokens stay unsplit (no partial
+// results at all); everything else is cut into partitions of 1024 tokens so that skewed
+// length mixes deal out evenly, coarsened if that would exceed the item budget.
 Plan make_plan(const lamina_attn_config &c)
 {
     Plan pl;
+    const long long pairs = (long long)c.max_batch * c.num_kv_heads;
     int P;
     if (c.num_splits >= 1) {
         P = c.num_splits;
+    } else if (c.max_seq_len <= 4096 && pairs >= 256) {
+        P = 1;
     } else {
-        const long long pairs = (long long)c.max_batch * c.num_kv_heads;
         int target = 1024;
-        if (pairs * ((c.max_seq_len + target - 1) / target) < 1024)
-            target = 512;
+        while (pairs * ((c.max_seq_len + target - 1) / target) > kMaxItems)
+            target *= 2;
         P = (c.max_seq_len + target - 1) / target;
-        if (P < 1)
-            P = 1;
     }
+    if (P < 1)
+        P = 1;
     int chunk = round_up((c.max_seq_len + P - 1) / P, kChunkAlign);
     if (chunk < kChunkAlign)
         chunk = kChunkAlign;
@@ -566,8 +758,12 @@ const char *check_config(const lamina_attn_config *c, int *code)
         return "group size num_q_heads/num_kv_heads must be 1, 2, 4, 8 or 16";
     if (c->kernel != LAMINA_KERNEL_MFMA)
         return "unknown kernel family";
-    if (c->num_splits > 4096)
-        return "num_splits above 4096";
+    if (c->num_splits > 1) {
+        if (c->max_batch > kMaxSplitBatch)
+            return "a partitioned handle supports max_batch up to 2048";
+        if ((long long)c->max_batch * c->num_kv_heads * c->num_splits > kMaxItems)
+            return "max_batch * num_kv_heads * num_splits above 65536";
+    }
     *code = LAMINA_OK;
     return nullptr;
 }
@@ -659,6 +855,24 @@ int lamina_attn_create(const lamina_attn_config *cfg, lamina_attn_t *out_handle)
     h->workspace = nullptr;
     h->workspace_bytes = workspace_bytes_for(*cfg, pl);
     h->err[0] = 0;
+    {
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device);
+        if (e != hipSuccess || cus <= 0) {
+            snprintf(g_create_err, sizeof g_create_err, "cannot query compute units: %s",
+                     hipGetErrorString(e));
+            delete h;
+            return LAMINA_ERR_HIP;
+        }
+        h->resident_wgs = 2 * cus;
+        if (pl.num_splits > 1 && (h->resident_wgs < kMinGrid || cfg->max_batch > kMaxSplitBatch)) {
+            snprintf(g_create_err, sizeof g_create_err,
+                     "partitioned handles need max_batch <= %d and a device with >= %lld compute units",
+                     kMaxSplitBatch, kMinGrid / 2);
+            delete h;
+            return LAMINA_ERR_UNSUPPORTED;
+        }
+    }
     if (h->workspace_bytes) {
         DeviceGuard guard(cfg->device);
         e = guard.ok() ? hipMalloc((void **)&h->workspace, h->workspace_bytes) : hipErrorInvalidDevice;
@@ -755,6 +969,7 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
     mp.G = h->group;
     mp.P = h->num_splits;
     mp.chunk = h->split_tokens;
+    mp.batch = p->batch;
     mp.out_is_bf16 = c.out_dtype == LAMINA_BF16;
     mp.scale_log2 = h->scale * kLog2e;
     if (h->num_splits > 1) {
@@ -766,9 +981,13 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
     if (!guard.ok())
         return fail(h, LAMINA_ERR_HIP, "cannot select the handle's device");
     hipStream_t stream = static_cast<hipStream_t>(p->stream);
-    const long long wgs = (long long)p->batch * c.num_kv_heads * h->num_splits;
-    if (wgs > 0x7fffffffLL)
-        return fail(h, LAMINA_ERR_UNSUPPORTED, "grid too large");
+    // Persistent grid: never more work-groups than can be resident, never more than items.
+    long long wgs = (long long)p->batch * c.num_kv_heads * h->num_splits;
+    if (wgs > h->resident_wgs)
+        wgs = h->resident_wgs;
+    if (h->num_splits == 1 &&
+        ((long long)p->batch * c.num_kv_heads + wgs - 1) / wgs > 0x3fffffffLL / kThreads)
+        return fail(h, LAMINA_ERR_UNSUPPORTED, "batch too large");
     const dim3 grid((unsigned)wgs), block(kThreads);
     if (fp8 && paged)
         hipLaunchKernelGGL((decode_mfma_kernel<true, true>), grid, block, 0, stream, mp);

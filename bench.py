@@ -27,6 +27,28 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 
+def read_traffic_summary(workload: str):
+    """HBM bytes per launch of the main kernel, as measured with rocprofv3 counters and
+    stored in the committed summary profiles/traffic_<workload>.txt (key = value lines:
+    fetch_bytes, write_bytes, already scaled by the copy-kernel calibration).  None if the
+    summary does not exist."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    with open(path) as f:
+        for line in f:
+            if "=" in line and not line.lstrip().startswith("#"):
+                k, v = line.split("=", 1)
+                try:
+                    vals[k.strip()] = float(v.split()[0])
+                except ValueError:
+                    pass
+    if "fetch_bytes" not in vals or "write_bytes" not in vals:
+        return None
+    return int(vals["fetch_bytes"] + vals["write_bytes"])
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,8 +67,9 @@ def main() -> int:
                     help="override the workload's cache dtype")
     ap.add_argument("--fixed-len", type=int, default=0,
                     help="override the workload's length mix: every context this long")
-    ap.add_argument("--no-events", action="store_true",
-                    help="do not record per-launch events inside the timed region")
+    ap.add_argument("--event-every", type=int, default=8,
+                    help="bracket every Nth launch of the timed region with HIP events "
+                         "(0: none).  Every launch costs ~6 us of stream time when bracketed.")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the operator, run a plain device copy of 1 GiB a few times "
                          "(reference reading for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -133,22 +156,28 @@ def main() -> int:
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    # Events are recorded on the stream the kernels are launched on (torch's current stream).
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for _ in range(args.steps)]
+    # Launch durations: HIP events on the stream the kernels are launched on (torch's current
+    # stream), around a sample of the launches inside the timed region.  Bracketing a launch
+    # inserts two stream markers (about 6 us), so only every Nth launch is bracketed and the
+    # whole region is timed by the host clock between two synchronisations.
+    sampled = ([i for i in range(args.steps) if i % args.event_every == args.event_every // 2]
+               if args.event_every > 0 else [])
+    ev = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for i in sampled}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        if not args.no_events:
+        if i in ev:
             ev[i][0].record()
-        step(i)
-        if not args.no_events:
+            step(i)
             ev[i][1].record()
+        else:
+            step(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    per_call_ms = (np.array([a.elapsed_time(bb) for a, bb in ev]) if not args.no_events
-                   else np.full(args.steps, wall * 1e3 / args.steps))
     ms_per_step = wall * 1e3 / args.steps
+    per_call_ms = (np.array([a.elapsed_time(bb) for a, bb in ev.values()]) if ev
+                   else np.full(1, ms_per_step))
 
     ab = W.algorithmic_bytes(w, lens, out_bytes=2 if args.out_dtype == "bf16" else 4,
                              num_splits=op.num_splits)
@@ -157,6 +186,7 @@ def main() -> int:
     kern_ms = float(per_call_ms.mean())
     kern_gbps = total_bytes / (kern_ms * 1e-3) / 1e9
 
+    traffic = read_traffic_summary(w.name)
     result = {
         "metric": "decode_attention_hbm_bandwidth",
         "value": round(gbps, 1),
@@ -183,9 +213,10 @@ def main() -> int:
         "parity_max_abs_err_sampled": max_err,
         "roofline": {"bound": "hbm", "achieved": round(kern_gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": None,
+                     "traffic": traffic,
                      "kernel": "decode_mfma_kernel" + (" + merge_partials_kernel"
                                                        if op.num_splits > 1 else ""),
+                     "launches_timed": int(len(per_call_ms)),
                      "launch_ms_mean": round(kern_ms, 5),
                      "launch_ms_median": round(float(np.median(per_call_ms)), 5),
                      "launch_ms_min": round(float(per_call_ms.min()), 5)},

@@ -112,6 +112,18 @@ __device__ __forceinline__ bf16x8 join_bf16x4(bf16x4 a, bf16x4 b)
     return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// Work-group barrier that orders LDS traffic only.  Unlike __syncthreads() it does not wait
+// for outstanding global loads or stores, so prefetched K/V tiles stay in flight across it.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Wait until every vector-memory operation this wavefront has issued is complete.
+__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 __device__ __forceinline__ void store_out(void *out, int out_is_bf16, size_t idx, float x)
 {
     if (out_is_bf16)
@@ -510,7 +522,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             f32x4 z = {0.f, 0.f, 0.f, 0.f};
             o_acc[db] = z;
         }
-        __syncthreads();
+        lds_barrier();
+        // The next item's first two tiles and its Q were requested before this point and have
+        // had the whole combine so far to arrive.  Waiting for them here -- before this item's
+        // result stores are issued -- leaves the tile loop with nothing but its own refills
+        // outstanding, which is what keeps its waits exact.
+        wait_vmem_all();
         const int len = lens[r];
         const bool whole = nparts(len) == 1;              // the request has no other partition
         float vs = 1.0f;
@@ -546,7 +563,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                     prm.part_lse[row * prm.P + c] = lse_nat;
             }
         }
-        __syncthreads();                                  // staging may be overwritten again
+        lds_barrier();                                    // staging may be overwritten again
     };
 
     // ---- stream -----------------------------------------------------------------------------
@@ -565,6 +582,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         __builtin_amdgcn_sched_barrier(0);
         load_q(nxt.r, nxt.g);
         c_log2 = score_scale(nxt.r, nxt.g);
+        wait_vmem_all();
     }
     for (int slot = 0; slot < nslots; ++slot) {
         if (nxt.slot == slot) {
@@ -598,10 +616,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             target(2, kb, vb, bt, rts, rlast);
             fetch_pages(bt, rts, rlast, pg);
             int ts = cur.t0w;
-            // Everything issued so far (this item's first two tiles and its Q, all requested
-            // while the previous item was being finished) is waited for here, so that inside
-            // the loop the only vector-memory operations ever outstanding are the refills.
-            __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0), other counters untouched
             for (int k = 0; k < n_even; k += 2) {
                 consume(kA, vA, sc);
                 __builtin_amdgcn_sched_barrier(0);
@@ -698,8 +712,9 @@ constexpr long long kMaxItems = kTableSlots * kMinGrid;
 
 // Partitioning.  Explicit num_splits is honoured.  Otherwise: batches that already hold one
 // item per resident work-group with contexts of at most 4096 tokens stay unsplit (no partial
-// results at all); everything else is cut into partitions of 1024 tokens so that skewed
-// length mixes deal out evenly, coarsened if that would exceed the item budget.
+// results at all); everything else is cut into partitions of 512 KiB of K+V per kv head
+// (1024 bf16 tokens, 2048 fp8 tokens) so that skewed length mixes deal out evenly,
+// coarsened if that would exceed the item budget.
 Plan make_plan(const lamina_attn_config &c)
 {
     Plan pl;
@@ -710,7 +725,7 @@ Plan make_plan(const lamina_attn_config &c)
     } else if (c.max_seq_len <= 4096 && pairs >= 256) {
         P = 1;
     } else {
-        int target = 1024;
+        int target = c.kv_dtype == LAMINA_FP8_E4M3 ? 2048 : 1024;
         while (pairs * ((c.max_seq_len + target - 1) / target) > kMaxItems)
             target *= 2;
         P = (c.max_seq_len + target - 1) / target;

@@ -44,7 +44,7 @@ constexpr int kWaves = 4;              // wavefronts per work-group
 constexpr int kThreads = kWaves * 64;
 constexpr int kChunkAlign = 256;       // partition sizes are multiples of 4 wavefronts x 64 tokens
 constexpr int kMaxGroup = 16;          // query heads per kv head the MFMA tile can hold
-constexpr int kMaxSplitBatch = 2048;   // requests per call when the KV range is partitioned
+constexpr int kMaxSplitBatch = 1024;   // requests per call when the KV range is partitioned
 constexpr int kTableSlots = 256;       // work items one work-group can be dealt per call
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -167,7 +167,7 @@ __device__ __forceinline__ void store_out(void *out, int out_is_bf16, size_t idx
 //            comes from a transposing LDS read.  The accumulator keeps head = col, so the
 //            running rescale is lane-local.
 // -------------------------------------------------------------------------------------------
-template <bool FP8, bool PAGED>
+template <bool FP8, bool PAGED, int GQ>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainParams prm)
 {
     constexpr int TILE = FP8 ? 64 : 32;                   // tokens per wavefront tile (16 KiB of K+V)
@@ -183,13 +183,17 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     constexpr int VBUF = TILE * VSTRIDE;                  // V staging bytes per wavefront
     constexpr bool SPLIT_P = !FP8;                        // carry p as hi + lo bf16 halves
     constexpr int step = kWaves * TILE;                   // token stride between a wave's tiles
-    // A wavefront's share of the end-of-item combine lives inside its own V staging area.
-    static_assert(kMaxGroup * (kHeadDim + 2) * 4 <= VBUF, "combine area must fit the staging");
+    constexpr int TRIP = kMaxGroup * kHeadDim + 2 * kMaxGroup;   // floats: O, then max, then sum
     static_assert(VR * RPI == TILE && KR % NSUB == 0, "tile geometry");
     __shared__ __attribute__((aligned(16))) unsigned char smem[kWaves * VBUF];
+    __shared__ __attribute__((aligned(16))) float s_trip[kWaves * TRIP];   // end-of-item triples
+    __shared__ int s_busy[kWaves];                        // 1 while s_trip[w] awaits the combine
+    __shared__ int s_count;                               // wavefronts that finished the item
     __shared__ int s_cum[kMaxSplitBatch + 1];             // partitions before request r
     __shared__ int s_tab_r[kTableSlots];                  // this work-group's items: request
     __shared__ int s_tab_c[kTableSlots];                  //                          partition
+    __shared__ int s_tab_len[kTableSlots];                //                          seq_lens[request]
+    __shared__ float s_wgt[kWaves * kMaxGroup];           // combine weights of the four triples
     __shared__ int s_wsum[kWaves];
 
     const int tid = threadIdx.x;
@@ -207,6 +211,13 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     const const_i32_ptr lens = (const_i32_ptr)prm.seq_lens;
 
     auto nparts = [&](int len) { return min(prm.P, max(1, (len + C - 1) / C)); };
+    unsigned char *vbuf = smem + w * VBUF;                // this wavefront's V staging area
+
+    if (tid < kWaves)
+        s_busy[tid] = 0;
+    if (tid == 0)
+        s_count = 0;
+    __syncthreads();
 
     // ---- the work list ---------------------------------------------------------------------
     int total_items;
@@ -262,6 +273,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             }
             s_tab_r[sl] = lo;
             s_tab_c[sl] = cidx - s_cum[lo];
+            s_tab_len[sl] = prm.seq_lens[lo];
         }
         __syncthreads();
     }
@@ -277,21 +289,22 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         const unsigned char *vbase;
         const_i32_ptr bt;
     };
-    auto identify = [&](int slot, int &r, int &g, int &c) {
+    auto identify = [&](int slot, int &r, int &g, int &c, int &len) {
         const int it = j + slot * nwg;
         g = it % Hkv;
         if (split) {
             r = __builtin_amdgcn_readfirstlane(s_tab_r[slot]);
             c = __builtin_amdgcn_readfirstlane(s_tab_c[slot]);
+            len = __builtin_amdgcn_readfirstlane(s_tab_len[slot]);
         } else {
             r = it / Hkv;
             c = 0;
+            len = lens[r];
         }
     };
     auto describe = [&](int slot, Desc &d) {
-        int r, g, c;
-        identify(slot, r, g, c);
-        const int len = lens[r];
+        int r, g, c, len;
+        identify(slot, r, g, c, len);
         d.slot = slot;
         d.r = r;
         d.g = g;
@@ -323,8 +336,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             }
         }
     };
-
-    unsigned char *vbuf = smem + w * VBUF;                // this wavefront's V staging area
 
     // Pool blocks of the 16-token pages of the tile starting at ts (wave-uniform scalar
     // loads), looked up one refill ahead of the loads that need them.
@@ -360,19 +371,35 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         }
     };
 
-    // Q as MFMA B operand: column = head col, k-step s holds 8 dims.
+    // Q as MFMA B operand: column = head col, k-step s holds 8 dims.  It is fetched as whole
+    // rows -- one 1 KiB load instruction per four heads, lane = (head, 16-byte piece) -- and
+    // turned into the operand layout through this wavefront's (idle between items) staging
+    // area, because vector-memory instructions, not bytes, are what an item boundary costs.
     bf16x8 qop[4];
-    auto load_q = [&](int r, int g) {
-        const __bf16 *qrow =
-            static_cast<const __bf16 *>(prm.q) + ((size_t)r * prm.Hq + g * G + col) * kHeadDim;
+    auto request_q = [&](int r, int g, u32x4(&raw)[GQ]) {
+        const unsigned char *qg = static_cast<const unsigned char *>(prm.q) +
+                                  ((size_t)r * prm.Hq + g * G) * (kHeadDim * 2);
+#pragma unroll
+        for (int i = 0; i < GQ; ++i) {
+            u32x4 z = {0u, 0u, 0u, 0u};
+            raw[i] = z;
+            if (i * 4 + (lane >> 4) < G)
+                raw[i] = *reinterpret_cast<const u32x4 *>(qg + (i * 4 + (lane >> 4)) * 256 +
+                                                          (lane & 15) * 16);
+        }
+    };
+    auto install_q = [&](const u32x4(&raw)[GQ]) {
+#pragma unroll
+        for (int i = 0; i < GQ; ++i)
+            *reinterpret_cast<u32x4 *>(vbuf + (i * 4 + (lane >> 4)) * 256 + (lane & 15) * 16) = raw[i];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             // The dims a lane holds in step s must be the dims its K register holds there.
             const int chunk8 = FP8 ? (((s >> 1) * 4 + quad) * 2 + (s & 1)) : (s * 4 + quad);
             bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
             qop[s] = z;
-            if (col < G)
-                qop[s] = *reinterpret_cast<const bf16x8 *>(qrow + chunk8 * 8);
+            if (col < GQ * 4)                             // rows at or above G hold zeros
+                qop[s] = *reinterpret_cast<const bf16x8 *>(vbuf + col * 256 + chunk8 * 16);
         }
     };
     auto score_scale = [&](int r, int g) {
@@ -496,23 +523,30 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         }
     };
 
-    // End of an item: the four wavefronts combine their triples (same identity as the
-    // cross-partition merge) and the work-group writes the item's result.
+    // End of an item for ONE wavefront.  Nobody waits at a barrier: the wavefront parks its
+    // (output, max, denominator) triple in LDS, counts itself in, and moves on to its next
+    // item; whichever of the four arrives last combines the triples (same identity as the
+    // cross-partition merge) and writes the item's result.  A wavefront can be at most one
+    // item ahead: it may not overwrite its parked triple before that item was combined.
     auto finalize = [&](int slot) {
-        int r, g, c;
-        identify(slot, r, g, c);
         l_run += __shfl_xor(l_run, 16);
         l_run += __shfl_xor(l_run, 32);
-        float *mo = reinterpret_cast<float *>(vbuf);      // [kMaxGroup][128] of this wavefront
-        float *mm = mo + kMaxGroup * kHeadDim;            // [kMaxGroup] running max
-        float *ml = mm + kMaxGroup;                       // [kMaxGroup] denominators
+        {
+            // (an LDS-typed pointer: a generic volatile read would be a FLAT load and drag the
+            //  vector-memory counter, i.e. the prefetched tiles, into the wait)
+            volatile __attribute__((address_space(3))) int *busy =
+                (volatile __attribute__((address_space(3))) int *)&s_busy[w];
+            while (*busy != 0)
+                __builtin_amdgcn_s_sleep(2);
+        }
+        float *mine = s_trip + w * TRIP;
         if (col < G) {
 #pragma unroll
             for (int db = 0; db < 8; ++db)
-                *reinterpret_cast<f32x4 *>(mo + col * kHeadDim + db * 16 + quad * 4) = o_acc[db];
+                *reinterpret_cast<f32x4 *>(mine + col * kHeadDim + db * 16 + quad * 4) = o_acc[db];
             if (quad == 0) {
-                mm[col] = m_run;
-                ml[col] = l_run;
+                mine[kMaxGroup * kHeadDim + col] = m_run;
+                mine[kMaxGroup * kHeadDim + kMaxGroup + col] = l_run;
             }
         }
         m_run = -INFINITY;
@@ -522,77 +556,115 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             f32x4 z = {0.f, 0.f, 0.f, 0.f};
             o_acc[db] = z;
         }
-        lds_barrier();
-        // The next item's first two tiles and its Q were requested before this point and have
-        // had the whole combine so far to arrive.  Waiting for them here -- before this item's
-        // result stores are issued -- leaves the tile loop with nothing but its own refills
-        // outstanding, which is what keeps its waits exact.
-        wait_vmem_all();
-        const int len = lens[r];
+        int arrived = 0;
+        if (lane == 0)
+            s_busy[w] = 1;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        if (lane == 0)
+            arrived = __hip_atomic_fetch_add(&s_count, 1, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_WORKGROUP);
+        arrived = __builtin_amdgcn_readfirstlane(arrived);
+        if (arrived != kWaves - 1)
+            return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        int r, g, c, len;
+        identify(slot, r, g, c, len);
         const bool whole = nparts(len) == 1;              // the request has no other partition
         float vs = 1.0f;
         if (FP8)
             vs = ((const __attribute__((address_space(4))) float *)prm.v_scale)[(size_t)r * Hkv + g];
-        for (int i = tid; i < G * kHeadDim; i += kThreads) {
-            const int h = i >> 7;
-            const int d = i & 127;
-            float M = -INFINITY;
-#pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww)
-                M = fmaxf(M, reinterpret_cast<const float *>(smem + ww * VBUF)[kMaxGroup * kHeadDim + h]);
-            float L = 0.0f, o = 0.0f;
-#pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) {
-                const float *wo = reinterpret_cast<const float *>(smem + ww * VBUF);
-                const float mw = wo[kMaxGroup * kHeadDim + h];
-                const float e = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);   // idle wavefront
-                L += e * wo[kMaxGroup * kHeadDim + kMaxGroup + h];
-                o += e * wo[h * kHeadDim + d];
-            }
+        {
+            // weights: lane = (head col, wavefront quad)
+            const float mw = s_trip[quad * TRIP + kMaxGroup * kHeadDim + col];
+            const float lw = s_trip[quad * TRIP + kMaxGroup * kHeadDim + kMaxGroup + col];
+            float M = fmaxf(mw, __shfl_xor(mw, 16));
+            M = fmaxf(M, __shfl_xor(M, 32));
+            const float e = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);   // idle wavefront
+            float L = e * lw;
+            L += __shfl_xor(L, 16);
+            L += __shfl_xor(L, 32);
             const bool empty = !(L > 0.0f);               // a request with no tokens at all
-            o = empty ? 0.0f : o / L * vs;
-            const float lse_nat = empty ? -INFINITY : (M + log2f(L)) * kLn2;
-            const size_t row = (size_t)r * prm.Hq + g * G + h;
-            if (whole) {
-                store_out(prm.out, prm.out_is_bf16, row * kHeadDim + d, o);
-                if (d == 0 && prm.lse)
-                    prm.lse[row] = lse_nat;
-            } else {
-                prm.part_out[(row * prm.P + c) * kHeadDim + d] = o;
-                if (d == 0)
+            s_wgt[quad * kMaxGroup + col] = empty ? 0.0f : e * vs * __builtin_amdgcn_rcpf(L);
+            if (quad == 0 && col < G) {
+                const float lse_nat = empty ? -INFINITY : (M + __builtin_amdgcn_logf(L)) * kLn2;
+                const size_t row = (size_t)r * prm.Hq + g * G + col;
+                if (whole) {
+                    if (prm.lse)
+                        prm.lse[row] = lse_nat;
+                } else {
                     prm.part_lse[row * prm.P + c] = lse_nat;
+                }
             }
         }
-        lds_barrier();                                    // staging may be overwritten again
+        // outputs: lane = four consecutive dims of one head, two heads per pass
+        for (int base = 0; base < G * 32; base += 64) {
+            const int idx = base + lane;
+            if (idx < G * 32) {
+                const int h = idx >> 5;
+                const int d4 = (idx & 31) * 4;
+                f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ww = 0; ww < kWaves; ++ww) {
+                    const f32x4 t =
+                        *reinterpret_cast<const f32x4 *>(s_trip + ww * TRIP + h * kHeadDim + d4);
+                    o += s_wgt[ww * kMaxGroup + h] * t;
+                }
+                const size_t row = (size_t)r * prm.Hq + g * G + h;
+                if (!whole) {
+                    *reinterpret_cast<f32x4 *>(prm.part_out + (row * prm.P + c) * kHeadDim + d4) = o;
+                } else if (prm.out_is_bf16) {
+                    u32x2 pk;
+                    pk[0] = (unsigned)bf16_bits(o[0]) | ((unsigned)bf16_bits(o[1]) << 16);
+                    pk[1] = (unsigned)bf16_bits(o[2]) | ((unsigned)bf16_bits(o[3]) << 16);
+                    *reinterpret_cast<u32x2 *>(static_cast<unsigned short *>(prm.out) +
+                                               row * kHeadDim + d4) = pk;
+                } else {
+                    *reinterpret_cast<f32x4 *>(static_cast<float *>(prm.out) + row * kHeadDim + d4) = o;
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        if (lane == 0)
+            s_count = 0;
+        if (lane < kWaves)
+            s_busy[lane] = 0;
     };
 
     // ---- stream -----------------------------------------------------------------------------
     u32x4 kA[KR], vA[VR], kB[KR], vB[VR];
     int pg[NSUB];
     f32x4 sc[NSUB];
+    u32x4 qn[GQ];                   // Q rows of the wavefront's next item, requested an item ahead
+    float cn = 0.0f;
     Desc nxt;
     find_next(0, nxt);
     if (nxt.slot >= 0) {
-        // prologue: the first two tile slots of this wavefront's first item
+        // prologue: the first two tile slots of this wavefront's first item, and its Q
         fetch_pages(nxt.bt, nxt.t0w, nxt.t1 - 1, pg);
         issue_loads(nxt.kbase, nxt.vbase, nxt.t0w, nxt.t1 - 1, pg, kA, vA);
         __builtin_amdgcn_sched_barrier(0);                // A must be the older set
         fetch_pages(nxt.bt, nxt.t0w + step, nxt.t1 - 1, pg);
         issue_loads(nxt.kbase, nxt.vbase, nxt.t0w + step, nxt.t1 - 1, pg, kB, vB);
         __builtin_amdgcn_sched_barrier(0);
-        load_q(nxt.r, nxt.g);
-        c_log2 = score_scale(nxt.r, nxt.g);
-        wait_vmem_all();
+        request_q(nxt.r, nxt.g, qn);
+        cn = score_scale(nxt.r, nxt.g);
+        wait_vmem_all();                                  // start-up only: nothing else to do yet
     }
     for (int slot = 0; slot < nslots; ++slot) {
         if (nxt.slot == slot) {
             // Sets A and B already hold (or are receiving) this item's first two tile slots.
             const Desc cur = nxt;
             cur_t1 = cur.t1;
+            c_log2 = cn;
+            install_q(qn);
             find_next(slot + 1, nxt);
             // Where refills go once this item's tiles are exhausted: the next item's first
             // two slots, or -- at the very end -- harmless reloads of this item's last row.
             const bool more = nxt.slot >= 0;
+            if (more) {
+                request_q(nxt.r, nxt.g, qn);              // needed one whole item from now
+                cn = score_scale(nxt.r, nxt.g);
+            }
             const unsigned char *n_kbase = more ? nxt.kbase : cur.kbase;
             const unsigned char *n_vbase = more ? nxt.vbase : cur.vbase;
             const const_i32_ptr n_bt = more ? nxt.bt : cur.bt;
@@ -635,10 +707,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                 finish(ts + step, sc);
                 __builtin_amdgcn_sched_barrier(0);
                 ts += 2 * step;
-            }
-            if (more) {
-                load_q(nxt.r, nxt.g);                     // lands while the item is combined
-                c_log2 = score_scale(nxt.r, nxt.g);
             }
         }
         finalize(slot);
@@ -775,7 +843,7 @@ const char *check_config(const lamina_attn_config *c, int *code)
         return "unknown kernel family";
     if (c->num_splits > 1) {
         if (c->max_batch > kMaxSplitBatch)
-            return "a partitioned handle supports max_batch up to 2048";
+            return "a partitioned handle supports max_batch up to 1024";
         if ((long long)c->max_batch * c->num_kv_heads * c->num_splits > kMaxItems)
             return "max_batch * num_kv_heads * num_splits above 65536";
     }
@@ -1004,14 +1072,26 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
         ((long long)p->batch * c.num_kv_heads + wgs - 1) / wgs > 0x3fffffffLL / kThreads)
         return fail(h, LAMINA_ERR_UNSUPPORTED, "batch too large");
     const dim3 grid((unsigned)wgs), block(kThreads);
+    // Kernel variant: cache dtype x layout x number of four-head Q row groups.
+    const int gq = h->group <= 4 ? 1 : (h->group <= 8 ? 2 : 4);
+#define LAMINA_LAUNCH(F8, PG)                                                                  \
+    do {                                                                                       \
+        if (gq == 1)                                                                           \
+            hipLaunchKernelGGL((decode_mfma_kernel<F8, PG, 1>), grid, block, 0, stream, mp);   \
+        else if (gq == 2)                                                                      \
+            hipLaunchKernelGGL((decode_mfma_kernel<F8, PG, 2>), grid, block, 0, stream, mp);   \
+        else                                                                                   \
+            hipLaunchKernelGGL((decode_mfma_kernel<F8, PG, 4>), grid, block, 0, stream, mp);   \
+    } while (0)
     if (fp8 && paged)
-        hipLaunchKernelGGL((decode_mfma_kernel<true, true>), grid, block, 0, stream, mp);
+        LAMINA_LAUNCH(true, true);
     else if (fp8)
-        hipLaunchKernelGGL((decode_mfma_kernel<true, false>), grid, block, 0, stream, mp);
+        LAMINA_LAUNCH(true, false);
     else if (paged)
-        hipLaunchKernelGGL((decode_mfma_kernel<false, true>), grid, block, 0, stream, mp);
+        LAMINA_LAUNCH(false, true);
     else
-        hipLaunchKernelGGL((decode_mfma_kernel<false, false>), grid, block, 0, stream, mp);
+        LAMINA_LAUNCH(false, false);
+#undef LAMINA_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail_hip(h, "main kernel launch", e);

@@ -78,6 +78,7 @@ struct MergeParams {
     void *out;
     float *lse;
     int Hq, P, chunk;
+    int rows;
     int out_is_bf16;
 };
 
@@ -182,6 +183,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     constexpr int RPI = 64 / LPR;                         // V rows per load instruction
     constexpr int VBUF = TILE * VSTRIDE;                  // V staging bytes per wavefront
     constexpr bool SPLIT_P = !FP8;                        // carry p as hi + lo bf16 halves
+    // Keep the next item's Q rows in registers for a whole item?  Only where the register
+    // file has room (not with the fp8 tile, not with 16 head rows); otherwise the rows are
+    // fetched when the item starts, which costs that wavefront one exposed cache latency.
+    constexpr bool Q_AHEAD = !FP8 && GQ <= 2;
     constexpr int step = kWaves * TILE;                   // token stride between a wave's tiles
     constexpr int TRIP = kMaxGroup * kHeadDim + 2 * kMaxGroup;   // floats: O, then max, then sum
     static_assert(VR * RPI == TILE && KR % NSUB == 0, "tile geometry");
@@ -350,24 +355,29 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     // touched; their scores are masked later.
     auto issue_loads = [&](const unsigned char *kbase, const unsigned char *vbase, int ts,
                            int last, const int(&pg)[NSUB], u32x4(&kr)[KR], u32x4(&vr)[VR]) {
+        // Addresses are a wave-uniform 64-bit base (request/head, or pool page) plus a 32-bit
+        // per-lane byte offset, which keeps address arithmetic and registers small.
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub) {
             const int tok = min(ts + sub * 16 + col, last);
-            const unsigned char *row =
-                PAGED ? kbase + (long long)pg[sub] * prm.pool_stride_block_b + (tok & 15) * ROWB
-                      : kbase + (long long)tok * prm.stride_tok_b;
+            const unsigned char *base =
+                PAGED ? kbase + (long long)pg[sub] * prm.pool_stride_block_b : kbase;
+            const unsigned off = PAGED ? (unsigned)((tok & 15) * ROWB + quad * 16)
+                                       : (unsigned)tok * (unsigned)prm.stride_tok_b + quad * 16;
 #pragma unroll
             for (int s = 0; s < KPS; ++s)
-                kr[sub * KPS + s] = load_stream_128(row + (s * 4 + quad) * 16);
+                kr[sub * KPS + s] = load_stream_128(base + off + s * 64);
         }
 #pragma unroll
         for (int i = 0; i < VR; ++i) {
             const int tok = min(ts + i * RPI + lane / LPR, last);
             const int sub = (i * RPI) / 16;               // compile-time per instruction
-            const unsigned char *row =
-                PAGED ? vbase + (long long)pg[sub] * prm.pool_stride_block_b + (tok & 15) * ROWB
-                      : vbase + (long long)tok * prm.stride_tok_b;
-            vr[i] = load_stream_128(row + (lane % LPR) * 16);
+            const unsigned char *base =
+                PAGED ? vbase + (long long)pg[sub] * prm.pool_stride_block_b : vbase;
+            const unsigned off = PAGED ? (unsigned)((tok & 15) * ROWB + (lane % LPR) * 16)
+                                       : (unsigned)tok * (unsigned)prm.stride_tok_b +
+                                             (lane % LPR) * 16;
+            vr[i] = load_stream_128(base + off);
         }
     };
 
@@ -646,7 +656,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         fetch_pages(nxt.bt, nxt.t0w + step, nxt.t1 - 1, pg);
         issue_loads(nxt.kbase, nxt.vbase, nxt.t0w + step, nxt.t1 - 1, pg, kB, vB);
         __builtin_amdgcn_sched_barrier(0);
-        request_q(nxt.r, nxt.g, qn);
+        if (Q_AHEAD)
+            request_q(nxt.r, nxt.g, qn);
         cn = score_scale(nxt.r, nxt.g);
         wait_vmem_all();                                  // start-up only: nothing else to do yet
     }
@@ -656,13 +667,18 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             const Desc cur = nxt;
             cur_t1 = cur.t1;
             c_log2 = cn;
+            if (!Q_AHEAD) {
+                request_q(cur.r, cur.g, qn);
+                wait_vmem_all();                          // also keeps the tile loop's waits exact
+            }
             install_q(qn);
             find_next(slot + 1, nxt);
             // Where refills go once this item's tiles are exhausted: the next item's first
             // two slots, or -- at the very end -- harmless reloads of this item's last row.
             const bool more = nxt.slot >= 0;
             if (more) {
-                request_q(nxt.r, nxt.g, qn);              // needed one whole item from now
+                if (Q_AHEAD)
+                    request_q(nxt.r, nxt.g, qn);          // needed one whole item from now
                 cn = score_scale(nxt.r, nxt.g);
             }
             const unsigned char *n_kbase = more ? nxt.kbase : cur.kbase;
@@ -716,15 +732,21 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
 // -------------------------------------------------------------------------------------------
 // Cross-partition merge (Sec. 4.2.2 identity, P parts, log-sum-exp form):
 //   lse = ln sum_p e^{lse_p},  out = sum_p e^{lse_p - lse} out_p.
-// One work-group of 128 threads per (request, query head); thread d owns output column d.
+// One wavefront per (request, query head) row, four rows per work-group; lane d owns output
+// columns 2d and 2d+1.  Lane p first holds partition p's weight (the log-sum-exp reduction is
+// two wave reductions), then all lanes stream the partial outputs with independent loads.
 // Only the first ceil(len / chunk) partitions were written by the main pass, and a request
 // with a single partition was already written to out/lse by the main pass.
 // -------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kHeadDim) void merge_partials_kernel(const MergeParams prm)
+constexpr int kMergeRowsPerBlock = 4;
+
+__global__ __launch_bounds__(64 * kMergeRowsPerBlock) void merge_partials_kernel(const MergeParams prm)
 {
-    const int row = blockIdx.x;                           // r * Hq + h
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * kMergeRowsPerBlock + (threadIdx.x >> 6);   // r * Hq + h
+    if (row >= prm.rows)
+        return;
     const int r = row / prm.Hq;
-    const int d = threadIdx.x;
     const int len = prm.seq_lens[r];
     const int np = min(prm.P, max(1, (len + prm.chunk - 1) / prm.chunk));
     if (np == 1)
@@ -732,16 +754,40 @@ __global__ __launch_bounds__(kHeadDim) void merge_partials_kernel(const MergePar
     const float *pl = prm.part_lse + (size_t)row * prm.P;
     const float *po = prm.part_out + (size_t)row * prm.P * kHeadDim;
     float M = -INFINITY;
-    for (int p = 0; p < np; ++p)
-        M = fmaxf(M, pl[p]);
-    float W = 0.0f, o = 0.0f;
-    for (int p = 0; p < np; ++p) {
-        const float e = __expf(pl[p] - M);
-        W += e;
-        o += e * po[(size_t)p * kHeadDim + d];
+    for (int p0 = 0; p0 < np; p0 += 64) {
+        const float v = (p0 + lane < np) ? pl[p0 + lane] : -INFINITY;
+        M = fmaxf(M, v);
     }
-    store_out(prm.out, prm.out_is_bf16, (size_t)row * kHeadDim + d, o / W);
-    if (d == 0 && prm.lse)
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        M = fmaxf(M, __shfl_xor(M, off));
+    float W = 0.0f;
+    float o0 = 0.0f, o1 = 0.0f;
+    for (int p0 = 0; p0 < np; p0 += 64) {
+        const float e = (p0 + lane < np) ? __expf(pl[p0 + lane] - M) : 0.0f;
+        W += e;
+        const int cnt = min(64, np - p0);
+#pragma unroll 4
+        for (int p = 0; p < cnt; ++p) {
+            const float w = __shfl(e, p);
+            const float2 t = *reinterpret_cast<const float2 *>(po + (size_t)(p0 + p) * kHeadDim +
+                                                              2 * lane);
+            o0 += w * t.x;
+            o1 += w * t.y;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        W += __shfl_xor(W, off);
+    const float inv = 1.0f / W;
+    const size_t at = (size_t)row * kHeadDim + 2 * lane;
+    if (prm.out_is_bf16) {
+        static_cast<unsigned *>(prm.out)[at >> 1] =
+            (unsigned)bf16_bits(o0 * inv) | ((unsigned)bf16_bits(o1 * inv) << 16);
+    } else {
+        *reinterpret_cast<float2 *>(static_cast<float *>(prm.out) + at) = make_float2(o0 * inv, o1 * inv);
+    }
+    if (lane == 0 && prm.lse)
         prm.lse[row] = M + logf(W);
 }
 
@@ -1030,6 +1076,9 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
             return fail(h, LAMINA_ERR_INVALID_ARG, "bad contiguous-cache strides");
     }
 
+    if (!paged && (long long)c.max_seq_len * p->kv_stride_tok * esz >= (1LL << 32))
+        return fail(h, LAMINA_ERR_UNSUPPORTED,
+                    "max_seq_len * kv_stride_tok must stay below 4 GiB per (request, kv head)");
     MainParams mp;
     memset(&mp, 0, sizeof mp);
     mp.q = q;
@@ -1106,8 +1155,10 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
         gp.P = h->num_splits;
         gp.chunk = h->split_tokens;
         gp.out_is_bf16 = mp.out_is_bf16;
-        hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(p->batch * c.num_q_heads)),
-                           dim3(kHeadDim), 0, stream, gp);
+        gp.rows = p->batch * c.num_q_heads;
+        hipLaunchKernelGGL(merge_partials_kernel,
+                           dim3((unsigned)((gp.rows + kMergeRowsPerBlock - 1) / kMergeRowsPerBlock)),
+                           dim3(64 * kMergeRowsPerBlock), 0, stream, gp);
         e = hipGetLastError();
         if (e != hipSuccess)
             return fail_hip(h, "merge kernel launch", e);

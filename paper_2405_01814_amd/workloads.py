@@ -62,6 +62,12 @@ WORKLOADS = {
                                 num_splits=64),
     "fp8_paged": Workload("fp8_paged", 5, 128, 64, 8, ("uniform", 1024, 16384),
                           kv_dtype="fp8", block_size=16),
+    # Multi-head attention (G = 1) shapes of the paper's other two evaluation models
+    # (Table "Large language models used for evaluation": LLaMA-65B d = 8192, LLaMA-33B
+    # d = 6656, both G = 1), as one attention device's head-level share (Sec. 5).
+    "llama_65b_mha_ctx4096": Workload("llama_65b_mha_ctx4096", 6, 64, 8, 8, ("fixed", 4096)),
+    "llama_33b_mha_paged": Workload("llama_33b_mha_paged", 7, 256, 13, 13,
+                                    ("lognormal", 1024, 0.8, 128, 16384), block_size=16),
 }
 
 

@@ -303,6 +303,17 @@ def test_full_llama3_70b_headshare_paged_all_rows():
     print("max abs err, lse err", e, flush=True)
 
 
+def test_full_mha_shapes_all_rows():
+    # G = 1: the paper's LLaMA-33B / 65B shapes, one attention device's head share
+    for name in ("llama_65b_mha_ctx4096", "llama_33b_mha_paged"):
+        print("generating", name, flush=True)
+        b = W.generate(W.WORKLOADS[name], threads=16)
+        got, info = gpu_of(b, max_seq_len=int(b["seq_lens"].max()))
+        print("partitioning", info, flush=True)
+        e = check(got, oracle_of(b), "bf16_f32")
+        print("max abs err, lse err", e, flush=True)
+
+
 def test_full_longctx_split64_sampled_rows():
     print("generating longctx_split64 (8 GiB)", flush=True)
     b = W.generate(W.WORKLOADS["longctx_split64"], threads=16)

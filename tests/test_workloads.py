@@ -60,6 +60,12 @@ def test_named_workloads_have_the_stated_shapes():
     assert len(l4) == 16 and (l4 == 131072).all()
     b4 = W.algorithmic_bytes(w["longctx_split64"], l4, num_splits=64)
     assert b4["kv"] == 8192 * 2 ** 20 and b4["partials"] == 2 * 16 * 32 * 64 * 129 * 4
+    assert w["llama_65b_mha_ctx4096"].group == 1 and w["llama_33b_mha_paged"].group == 1
+    # 64 and 52 heads of 128 (d = 8192 and 6656) over 8 and 4 attention devices
+    assert w["llama_65b_mha_ctx4096"].num_q_heads * 8 * 128 == 8192
+    assert w["llama_33b_mha_paged"].num_q_heads * 4 * 128 == 6656
+    l7 = W.draw_lens(w["llama_33b_mha_paged"])
+    assert len(l7) == 256 and l7.min() >= 128 and l7.max() <= 16384
     l5 = W.draw_lens(w["fp8_paged"])
     assert len(l5) == 128 and l5.min() >= 1024 and l5.max() <= 16384
 

@@ -154,6 +154,44 @@ size_t lamina_attn_workspace_bytes(const lamina_attn_config *cfg);
 int lamina_attn_num_splits(lamina_attn_t h);
 int lamina_attn_split_tokens(lamina_attn_t h);
 
+/*
+ * The two steps either side of the hot path on the attention device when the new token's
+ * k, v arrive after its q (Sec. 4.2.2, "resource utilization overlapping": the token set
+ * is split into all previous tokens and the newly generated one; [A_q(prev), S_q(prev)] is
+ * computed as soon as q is there -- that is lamina_decode_attention with seq_lens counting
+ * the previous tokens only, fp32 output and lse -- and k_n, v_n are folded in afterwards).
+ *
+ * lamina_append_kv writes the new token's rows into the cache:
+ *   k_new, v_new  device bf16 [R][num_kv_heads][128], dense
+ *   positions     device int32 [R]: token index the rows go to (normally the request's
+ *                 previous length); in paged mode block_table[r][positions[r] / 16] must
+ *                 already name the destination block
+ *   k_cache, v_cache, block_table, p: as for lamina_decode_attention (p->k_scale / v_scale
+ *                 are required for fp8 caches: bytes = e4m3fn(round-to-nearest-even(x / scale)),
+ *                 saturating at +-448)
+ * positions[r] < 0 skips request r.  Nothing else in the cache is touched.
+ *
+ * lamina_fold_new_token combines a result over the previous tokens with the single new token:
+ *   q             device bf16 [R][num_q_heads][128]
+ *   k_new, v_new  device bf16 [R][num_kv_heads][128]
+ *   out_prev      device fp32 [R][num_q_heads][128], lse_prev device fp32 [R][num_q_heads]:
+ *                 A_q(prev) and ln S_q(prev); lse_prev = -inf (no previous tokens) is allowed
+ *   out           device [R][num_q_heads][128] of out_dtype, lse device fp32 or NULL
+ * With s = scale * <q, k_new>:  lse = ln(e^{lse_prev} + e^s),
+ *   out = (e^{lse_prev} out_prev + e^s v_new) / (e^{lse_prev} + e^s)      (Sec. 4.2.2 identity).
+ * For fp8 handles k_new and v_new enter as the cache will hold them (quantised with
+ * p->k_scale / p->v_scale, then dequantised), so the result equals one call over the
+ * appended cache.  out may alias out_prev only if out_dtype is fp32.
+ *
+ * Both only enqueue work on p->stream.  Errors as for lamina_decode_attention.
+ */
+int lamina_append_kv(lamina_attn_t h, const void *k_new, const void *v_new, void *k_cache,
+                     void *v_cache, const int32_t *positions, const int32_t *block_table,
+                     const lamina_call_params *p);
+int lamina_fold_new_token(lamina_attn_t h, const void *q, const void *k_new, const void *v_new,
+                          const float *out_prev, const float *lse_prev, void *out, float *lse,
+                          const lamina_call_params *p);
+
 #ifdef __cplusplus
 }
 #endif

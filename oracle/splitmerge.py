@@ -49,3 +49,12 @@ def merge_lse_form(parts):
     for A, l in parts:
         out = out + np.exp(l - lse) * A
     return out, lse
+
+
+def fold_new_token(q_row, k_new, v_new, out_prev, lse_prev, scale):
+    """The prev/new split of Sec. 4.2.2: I = prev u {new}.  The new token alone has
+    A_q({new}) = v_new and ln S_q({new}) = scale * <q, k_new>; combine it with the given
+    (A_q(prev), ln S_q(prev)).  Returns (A_q(I), ln S_q(I))."""
+    s = scale * float(np.dot(np.asarray(q_row, dtype=np.float64), np.asarray(k_new, dtype=np.float64)))
+    return merge_lse_form([(np.asarray(out_prev, dtype=np.float64), float(lse_prev)),
+                           (np.asarray(v_new, dtype=np.float64), s)])

@@ -791,6 +791,139 @@ __global__ __launch_bounds__(64 * kMergeRowsPerBlock) void merge_partials_kernel
         prm.lse[row] = M + logf(W);
 }
 
+// -------------------------------------------------------------------------------------------
+// The new token's rows (Sec. 4.2.2: k_n, v_n arrive after q_n).
+// -------------------------------------------------------------------------------------------
+struct NewTokenParams {
+    const unsigned short *q;           // bf16 [R][Hq][128]        (fold only)
+    const unsigned short *k_new;       // bf16 [R][Hkv][128]
+    const unsigned short *v_new;
+    unsigned char *k_cache;            // append only
+    unsigned char *v_cache;
+    const int32_t *positions;
+    const int32_t *block_table;
+    const float *k_scale;
+    const float *v_scale;
+    const float *out_prev;             // fold only
+    const float *lse_prev;
+    void *out;
+    float *lse;
+    long long stride_req_b, stride_head_b, stride_tok_b;
+    long long pool_stride_block_b, pool_stride_head_b;
+    int bt_stride;
+    int Hq, Hkv, G;
+    int rows;                          // append: R * Hkv, fold: R * Hq
+    int fp8, paged, out_is_bf16;
+    float scale;
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(unsigned short b)
+{
+    return __builtin_bit_cast(float, (unsigned)b << 16);
+}
+
+// x -> the value an fp8 cache holds for it: e4m3fn(rne(x / scale)) (saturating), as a byte.
+__device__ __forceinline__ unsigned char quantise_e4m3fn(float x, float inv_scale)
+{
+    const float y = fminf(fmaxf(x * inv_scale, -448.0f), 448.0f);
+    return (unsigned char)(__builtin_amdgcn_cvt_pk_fp8_f32(y, 0.0f, 0, false) & 0xFF);
+}
+
+__device__ __forceinline__ float dequantise_e4m3fn(unsigned char b, float scale)
+{
+    const bf16x2 v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)b, 1.0f, false);
+    return static_cast<float>(v[0]) * scale;
+}
+
+// One wavefront per (request, kv head): lane i moves elements 2i and 2i+1 of the K and V rows.
+__global__ __launch_bounds__(256) void append_kv_kernel(const NewTokenParams prm)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);   // r * Hkv + g
+    if (row >= prm.rows)
+        return;
+    const int r = row / prm.Hkv;
+    const int g = row % prm.Hkv;
+    const int pos = prm.positions[r];
+    if (pos < 0)
+        return;
+    const int esz = prm.fp8 ? 1 : 2;
+    long long off;
+    if (prm.paged) {
+        const long long blk = prm.block_table[(size_t)r * prm.bt_stride + (pos >> 4)];
+        off = blk * prm.pool_stride_block_b + (long long)g * prm.pool_stride_head_b +
+              (long long)(pos & 15) * kHeadDim * esz;
+    } else {
+        off = (long long)r * prm.stride_req_b + (long long)g * prm.stride_head_b +
+              (long long)pos * prm.stride_tok_b;
+    }
+    const unsigned kk = reinterpret_cast<const unsigned *>(prm.k_new)[(size_t)row * 64 + lane];
+    const unsigned vv = reinterpret_cast<const unsigned *>(prm.v_new)[(size_t)row * 64 + lane];
+    if (!prm.fp8) {
+        reinterpret_cast<unsigned *>(prm.k_cache + off)[lane] = kk;
+        reinterpret_cast<unsigned *>(prm.v_cache + off)[lane] = vv;
+    } else {
+        const float iks = 1.0f / prm.k_scale[row];
+        const float ivs = 1.0f / prm.v_scale[row];
+        const unsigned short kq =
+            (unsigned short)quantise_e4m3fn(bf16_bits_to_float(kk & 0xFFFF), iks) |
+            ((unsigned short)quantise_e4m3fn(bf16_bits_to_float(kk >> 16), iks) << 8);
+        const unsigned short vq =
+            (unsigned short)quantise_e4m3fn(bf16_bits_to_float(vv & 0xFFFF), ivs) |
+            ((unsigned short)quantise_e4m3fn(bf16_bits_to_float(vv >> 16), ivs) << 8);
+        reinterpret_cast<unsigned short *>(prm.k_cache + off)[lane] = kq;
+        reinterpret_cast<unsigned short *>(prm.v_cache + off)[lane] = vq;
+    }
+}
+
+// One wavefront per (request, query head): the two-part case of the Sec. 4.2.2 identity with
+// I1 = previous tokens (given as A, ln S) and I2 = {new token} (A = v_new, ln S = s).
+__global__ __launch_bounds__(256) void fold_new_token_kernel(const NewTokenParams prm)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);   // r * Hq + h
+    if (row >= prm.rows)
+        return;
+    const int r = row / prm.Hq;
+    const int g = (row % prm.Hq) / prm.G;
+    const size_t kvrow = (size_t)r * prm.Hkv + g;
+    const unsigned qq = reinterpret_cast<const unsigned *>(prm.q)[(size_t)row * 64 + lane];
+    const unsigned kk = reinterpret_cast<const unsigned *>(prm.k_new)[kvrow * 64 + lane];
+    const unsigned vv = reinterpret_cast<const unsigned *>(prm.v_new)[kvrow * 64 + lane];
+    float k0 = bf16_bits_to_float(kk & 0xFFFF), k1 = bf16_bits_to_float(kk >> 16);
+    float v0 = bf16_bits_to_float(vv & 0xFFFF), v1 = bf16_bits_to_float(vv >> 16);
+    if (prm.fp8) {
+        const float ks = prm.k_scale[kvrow], vs = prm.v_scale[kvrow];
+        k0 = dequantise_e4m3fn(quantise_e4m3fn(k0, 1.0f / ks), ks);
+        k1 = dequantise_e4m3fn(quantise_e4m3fn(k1, 1.0f / ks), ks);
+        v0 = dequantise_e4m3fn(quantise_e4m3fn(v0, 1.0f / vs), vs);
+        v1 = dequantise_e4m3fn(quantise_e4m3fn(v1, 1.0f / vs), vs);
+    }
+    float dot = bf16_bits_to_float(qq & 0xFFFF) * k0 + bf16_bits_to_float(qq >> 16) * k1;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        dot += __shfl_xor(dot, off);
+    const float s = dot * prm.scale;
+    const float lp = prm.lse_prev[row];
+    const float m = fmaxf(lp, s);                         // s is finite, so m is
+    const float wp = (lp == -INFINITY) ? 0.0f : __expf(lp - m);
+    const float wn = __expf(s - m);
+    const float inv = 1.0f / (wp + wn);
+    const float2 op = wp > 0.0f
+                          ? *reinterpret_cast<const float2 *>(prm.out_prev + (size_t)row * kHeadDim + 2 * lane)
+                          : make_float2(0.0f, 0.0f);
+    const float o0 = (wp * op.x + wn * v0) * inv;
+    const float o1 = (wp * op.y + wn * v1) * inv;
+    const size_t at = (size_t)row * kHeadDim + 2 * lane;
+    if (prm.out_is_bf16)
+        static_cast<unsigned *>(prm.out)[at >> 1] =
+            (unsigned)bf16_bits(o0) | ((unsigned)bf16_bits(o1) << 16);
+    else
+        *reinterpret_cast<float2 *>(static_cast<float *>(prm.out) + at) = make_float2(o0, o1);
+    if (lane == 0 && prm.lse)
+        prm.lse[row] = m + logf(wp + wn);
+}
+
 }  // namespace
 
 // ============================================================================================
@@ -1163,6 +1296,140 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
         if (e != hipSuccess)
             return fail_hip(h, "merge kernel launch", e);
     }
+    return LAMINA_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Shared argument checks of the two new-token entry points.  Returns nullptr if fine.
+const char *check_new_token_args(const lamina_attn *h, const lamina_call_params *p, bool need_layout,
+                                 const void *block_table)
+{
+    const lamina_attn_config &c = h->cfg;
+    if (!p)
+        return "call params are NULL";
+    if (p->batch < 0 || p->batch > c.max_batch)
+        return "batch is negative or exceeds max_batch";
+    if (c.kv_dtype == LAMINA_FP8_E4M3 && (!p->k_scale || !p->v_scale))
+        return "fp8 cache needs k_scale and v_scale";
+    if (!need_layout)
+        return nullptr;
+    const int esz = c.kv_dtype == LAMINA_FP8_E4M3 ? 1 : 2;
+    if (c.block_size != 0) {
+        if (!block_table)
+            return "paged cache needs a block_table";
+        if (p->pool_stride_head < (long long)c.block_size * kHeadDim || p->pool_stride_block <= 0 ||
+            p->block_table_stride <= 0 || (p->pool_stride_head * esz) % 16 != 0 ||
+            (p->pool_stride_block * esz) % 16 != 0)
+            return "bad pool strides or block_table_stride";
+    } else if (p->kv_stride_tok < kHeadDim || p->kv_stride_req < 0 || p->kv_stride_head < 0 ||
+               (p->kv_stride_tok * esz) % 16 != 0 || (p->kv_stride_req * esz) % 16 != 0 ||
+               (p->kv_stride_head * esz) % 16 != 0) {
+        return "bad contiguous-cache strides";
+    }
+    return nullptr;
+}
+
+void fill_new_token_params(const lamina_attn *h, const lamina_call_params *p, NewTokenParams &np)
+{
+    const lamina_attn_config &c = h->cfg;
+    const int esz = c.kv_dtype == LAMINA_FP8_E4M3 ? 1 : 2;
+    memset(&np, 0, sizeof np);
+    np.k_scale = p->k_scale;
+    np.v_scale = p->v_scale;
+    np.stride_req_b = p->kv_stride_req * esz;
+    np.stride_head_b = p->kv_stride_head * esz;
+    np.stride_tok_b = p->kv_stride_tok * esz;
+    np.pool_stride_block_b = p->pool_stride_block * esz;
+    np.pool_stride_head_b = p->pool_stride_head * esz;
+    np.bt_stride = p->block_table_stride;
+    np.Hq = c.num_q_heads;
+    np.Hkv = c.num_kv_heads;
+    np.G = h->group;
+    np.fp8 = c.kv_dtype == LAMINA_FP8_E4M3;
+    np.paged = c.block_size != 0;
+    np.out_is_bf16 = c.out_dtype == LAMINA_BF16;
+    np.scale = h->scale;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lamina_append_kv(lamina_attn_t h, const void *k_new, const void *v_new, void *k_cache,
+                     void *v_cache, const int32_t *positions, const int32_t *block_table,
+                     const lamina_call_params *p)
+{
+    if (!h)
+        return LAMINA_ERR_INVALID_ARG;
+    h->err[0] = 0;
+    if (const char *msg = check_new_token_args(h, p, true, block_table))
+        return fail(h, LAMINA_ERR_INVALID_ARG, msg);
+    if (p->batch == 0)
+        return LAMINA_OK;
+    if (!k_new || !v_new || !k_cache || !v_cache || !positions)
+        return fail(h, LAMINA_ERR_INVALID_ARG,
+                    "k_new, v_new, k_cache, v_cache and positions must be non-NULL");
+    if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)k_cache | (uintptr_t)v_cache) % 16 != 0)
+        return fail(h, LAMINA_ERR_INVALID_ARG, "k_new, v_new and the caches must be 16-byte aligned");
+    NewTokenParams np;
+    fill_new_token_params(h, p, np);
+    np.k_new = static_cast<const unsigned short *>(k_new);
+    np.v_new = static_cast<const unsigned short *>(v_new);
+    np.k_cache = static_cast<unsigned char *>(k_cache);
+    np.v_cache = static_cast<unsigned char *>(v_cache);
+    np.positions = positions;
+    np.block_table = block_table;
+    np.rows = p->batch * h->cfg.num_kv_heads;
+    DeviceGuard guard(h->cfg.device);
+    if (!guard.ok())
+        return fail(h, LAMINA_ERR_HIP, "cannot select the handle's device");
+    hipLaunchKernelGGL(append_kv_kernel, dim3((unsigned)((np.rows + 3) / 4)), dim3(256), 0,
+                       static_cast<hipStream_t>(p->stream), np);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail_hip(h, "append kernel launch", e);
+    return LAMINA_OK;
+}
+
+int lamina_fold_new_token(lamina_attn_t h, const void *q, const void *k_new, const void *v_new,
+                          const float *out_prev, const float *lse_prev, void *out, float *lse,
+                          const lamina_call_params *p)
+{
+    if (!h)
+        return LAMINA_ERR_INVALID_ARG;
+    h->err[0] = 0;
+    if (const char *msg = check_new_token_args(h, p, false, nullptr))
+        return fail(h, LAMINA_ERR_INVALID_ARG, msg);
+    if (p->batch == 0)
+        return LAMINA_OK;
+    if (!q || !k_new || !v_new || !out_prev || !lse_prev || !out)
+        return fail(h, LAMINA_ERR_INVALID_ARG,
+                    "q, k_new, v_new, out_prev, lse_prev and out must be non-NULL");
+    if (((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)out_prev | (uintptr_t)out) % 8 != 0)
+        return fail(h, LAMINA_ERR_INVALID_ARG, "tensors must be 8-byte aligned");
+    if ((const void *)out_prev == (const void *)out && h->cfg.out_dtype != LAMINA_F32)
+        return fail(h, LAMINA_ERR_INVALID_ARG, "out may alias out_prev only for fp32 output");
+    NewTokenParams np;
+    fill_new_token_params(h, p, np);
+    np.q = static_cast<const unsigned short *>(q);
+    np.k_new = static_cast<const unsigned short *>(k_new);
+    np.v_new = static_cast<const unsigned short *>(v_new);
+    np.out_prev = out_prev;
+    np.lse_prev = lse_prev;
+    np.out = out;
+    np.lse = lse;
+    np.rows = p->batch * h->cfg.num_q_heads;
+    DeviceGuard guard(h->cfg.device);
+    if (!guard.ok())
+        return fail(h, LAMINA_ERR_HIP, "cannot select the handle's device");
+    hipLaunchKernelGGL(fold_new_token_kernel, dim3((unsigned)((np.rows + 3) / 4)), dim3(256), 0,
+                       static_cast<hipStream_t>(p->stream), np);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail_hip(h, "fold kernel launch", e);
     return LAMINA_OK;
 }
 

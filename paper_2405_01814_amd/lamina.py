@@ -27,7 +27,7 @@ LAMINA_KERNEL_MFMA, LAMINA_KERNEL_VALU = 0, 1
 
 EXPORTS = ("lamina_attn_create", "lamina_decode_attention", "lamina_attn_destroy",
            "lamina_attn_last_error", "lamina_attn_workspace_bytes", "lamina_attn_num_splits",
-           "lamina_attn_split_tokens")
+           "lamina_attn_split_tokens", "lamina_append_kv", "lamina_fold_new_token")
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -91,6 +91,11 @@ def load():
     lib.lamina_attn_num_splits.argtypes = [vp]
     lib.lamina_attn_split_tokens.restype = ctypes.c_int
     lib.lamina_attn_split_tokens.argtypes = [vp]
+    lib.lamina_append_kv.restype = ctypes.c_int
+    lib.lamina_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(lamina_call_params)]
+    lib.lamina_fold_new_token.restype = ctypes.c_int
+    lib.lamina_fold_new_token.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp,
+                                          ctypes.POINTER(lamina_call_params)]
     _lib = lib
     return lib
 
@@ -115,6 +120,18 @@ def lamina_decode_attention(h, q, k_cache, v_cache, seq_lens, block_table, out, 
     """Pointers are integers (device addresses) or None."""
     return load().lamina_decode_attention(h, q, k_cache, v_cache, seq_lens, block_table, out,
                                           lse, ctypes.byref(params) if params is not None else None)
+
+
+def lamina_append_kv(h, k_new, v_new, k_cache, v_cache, positions, block_table,
+                     params: lamina_call_params) -> int:
+    return load().lamina_append_kv(h, k_new, v_new, k_cache, v_cache, positions, block_table,
+                                   ctypes.byref(params) if params is not None else None)
+
+
+def lamina_fold_new_token(h, q, k_new, v_new, out_prev, lse_prev, out, lse,
+                          params: lamina_call_params) -> int:
+    return load().lamina_fold_new_token(h, q, k_new, v_new, out_prev, lse_prev, out, lse,
+                                        ctypes.byref(params) if params is not None else None)
 
 
 def lamina_attn_destroy(h) -> int:
@@ -194,6 +211,40 @@ class DecodeAttention:
             self.handle, q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(),
             seq_lens.data_ptr(), block_table.data_ptr() if block_table is not None else None,
             out.data_ptr(), lse.data_ptr() if lse is not None else None, p)
+        if rc != LAMINA_OK:
+            raise LaminaError(rc, lamina_attn_last_error(self.handle))
+        return out, lse
+
+    def append_kv(self, k_new, v_new, k_cache, v_cache, positions, block_table=None,
+                  k_scale=None, v_scale=None, stream=None):
+        """Write the new token's rows (bf16 [R][Hkv][128]) into the cache at positions[r]."""
+        p = self.params_for(k_new, k_cache, block_table, k_scale, v_scale, stream)
+        rc = lamina_append_kv(self.handle, k_new.data_ptr(), v_new.data_ptr(), k_cache.data_ptr(),
+                              v_cache.data_ptr(), positions.data_ptr(),
+                              block_table.data_ptr() if block_table is not None else None, p)
+        if rc != LAMINA_OK:
+            raise LaminaError(rc, lamina_attn_last_error(self.handle))
+
+    def fold_new_token(self, q, k_new, v_new, out_prev, lse_prev, out=None, lse=None,
+                       k_scale=None, v_scale=None, stream=None):
+        """Combine a result over the previous tokens with the single new token."""
+        import torch
+        R, Hq, D = q.shape
+        if out is None:
+            out = torch.empty((R, Hq, D), device=q.device,
+                              dtype=torch.float32 if self.out_dtype == "f32" else torch.bfloat16)
+        if lse is None:
+            lse = torch.empty((R, Hq), device=q.device, dtype=torch.float32)
+        p = lamina_call_params()
+        p.batch = R
+        p.k_scale = k_scale.data_ptr() if k_scale is not None else None
+        p.v_scale = v_scale.data_ptr() if v_scale is not None else None
+        if stream is None:
+            stream = torch.cuda.current_stream(q.device)
+        p.stream = stream.cuda_stream or None
+        rc = lamina_fold_new_token(self.handle, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                   out_prev.data_ptr(), lse_prev.data_ptr(), out.data_ptr(),
+                                   lse.data_ptr(), p)
         if rc != LAMINA_OK:
             raise LaminaError(rc, lamina_attn_last_error(self.handle))
         return out, lse

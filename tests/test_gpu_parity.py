@@ -339,3 +339,83 @@ def test_full_fp8_paged_sampled_rows():
     print("max abs err, lse err", e, flush=True)
     out, lse = got
     assert np.isfinite(out).all() and np.isfinite(lse).all()
+
+
+# ---- the new token's path: append k_n, v_n and fold them into a result over prev -----------
+
+def _append_reference(b, k_new, v_new, positions):
+    """Host-side expected cache after the append (bf16: the rows; fp8: oracle-encoded bytes)."""
+    w = b["workload"]
+    k, v = b["k"].clone(), b["v"].clone()
+    R, Hkv = k_new.shape[:2]
+    for r in range(R):
+        pos = int(positions[r])
+        if pos < 0:
+            continue
+        for g in range(Hkv):
+            for dst, src, sc in ((k, k_new, b.get("k_scale")), (v, v_new, b.get("v_scale"))):
+                if w.block_size:
+                    row = dst[int(b["block_table"][r, pos // 16]), g, pos % 16]
+                else:
+                    row = dst[r, g, pos]
+                if w.kv_dtype == "bf16":
+                    row.copy_(src[r, g])
+                else:
+                    x = (src[r, g].double() / sc[r, g].double()).tolist()
+                    row.view(torch.uint8).copy_(torch.tensor(
+                        [oracle.e4m3fn_encode(float(np.float32(xi))) for xi in x], dtype=torch.uint8))
+    return k, v
+
+
+@pytest.mark.parametrize("name", ["llama3_8b_ctx4096", "llama3_70b_headshare_paged", "fp8_paged"])
+def test_append_then_two_phase_equals_one_phase(name):
+    # Caches hold the previous tokens; the new token arrives separately (prev/new split).
+    lens_prev = np.array([0, 1, 15, 16, 100, 511, 700], dtype=np.int32)
+    w = W.WORKLOADS[name]
+    import dataclasses
+    b = W.generate(dataclasses.replace(w), lens=lens_prev + 1)      # room for the new token
+    R = len(lens_prev)
+    d = dev()
+    g = torch.Generator().manual_seed(77)
+    k_new = torch.randn(R, w.num_kv_heads, 128, generator=g).to(torch.bfloat16)
+    v_new = torch.randn(R, w.num_kv_heads, 128, generator=g).to(torch.bfloat16)
+    positions = torch.from_numpy(lens_prev.copy())
+    positions_skip = positions.clone()
+    t = {key: val.to(d) for key, val in b.items() if isinstance(val, torch.Tensor)}
+    op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=R, max_seq_len=1024,
+                                kv_dtype=w.kv_dtype, out_dtype="f32", block_size=w.block_size,
+                                num_splits=2)
+    # phase 1: attention over the previous tokens only (the new row in the cache is stale)
+    out_prev, lse_prev = op(t["q"], t["k"], t["v"], positions.to(d), block_table=t.get("block_table"),
+                            k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))
+    # phase 2: fold the new token in, without touching the cache
+    out2, lse2 = op.fold_new_token(t["q"], k_new.to(d), v_new.to(d), out_prev, lse_prev,
+                                   k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))
+    # append, bit-exact against the host reference
+    op.append_kv(k_new.to(d), v_new.to(d), t["k"], t["v"], positions.to(d),
+                 block_table=t.get("block_table"), k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))
+    torch.cuda.synchronize()
+    k_ref, v_ref = _append_reference(b, k_new, v_new, positions)
+    iv = torch.uint8 if w.kv_dtype == "fp8" else torch.int16
+    # compare only bytes that are defined (everything but poisoned padding is identical anyway)
+    assert torch.equal(t["k"].cpu().view(iv), k_ref.view(iv))
+    assert torch.equal(t["v"].cpu().view(iv), v_ref.view(iv))
+    # one phase over the appended cache
+    out1, lse1 = op(t["q"], t["k"], t["v"], t["seq_lens"], block_table=t.get("block_table"),
+                    k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))
+    torch.cuda.synchronize()
+    # oracle over the appended host cache
+    b2 = dict(b)
+    b2["k"], b2["v"] = k_ref, v_ref
+    ref = oracle_of(b2)
+    kind = "fp8" if w.kv_dtype == "fp8" else "bf16_f32"
+    check((out1.cpu().double().numpy(), lse1.cpu().double().numpy()), ref, kind)
+    check((out2.cpu().double().numpy(), lse2.cpu().double().numpy()), ref, kind)
+    # skipping a request (position -1) leaves its rows alone
+    positions_skip[:] = -1
+    before = t["k"].clone()
+    op.append_kv(v_new.to(d), k_new.to(d), t["k"], t["v"], positions_skip.to(d),
+                 block_table=t.get("block_table"), k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))
+    torch.cuda.synchronize()
+    assert torch.equal(before.view(iv), t["k"].view(iv))
+    op.close()

@@ -359,3 +359,23 @@ def test_strided_cache_views_are_honoured():
     big_v[:, :, :12, :D] = v
     o, l = run(q, big_k[:, :, :, :D], big_v[:, :, :, :D], lens_t, 2)
     assert np.array_equal(o, out) and np.array_equal(l, lse)
+
+
+# prev/new split --------------------------------------------------------------------------
+def test_fold_new_token_equals_attention_over_all_tokens():
+    n = 57
+    q, k, v, lens = rand_batch(21, 2, 4, 2, [n, 1])
+    out, lse = run(q, k, v, lens, 2)
+    prev = torch.tensor([n - 1, 0], dtype=torch.int32)
+    po, pl = run(q, k, v, prev, 2)                        # request 1 has no previous tokens
+    assert np.isneginf(pl[1]).all()
+    for r, m in enumerate([n, 1]):
+        for h in range(4):
+            g = h // 2
+            for merge_input_lse in (pl[r, h],):
+                o, l = splitmerge.fold_new_token(q[r, h].double().numpy(),
+                                                 k[r, g, m - 1].double().numpy(),
+                                                 v[r, g, m - 1].double().numpy(),
+                                                 po[r, h], merge_input_lse, SCALE)
+                assert np.abs(o - out[r, h]).max() <= 1e-13
+                assert abs(l - lse[r, h]) <= 1e-13

@@ -65,6 +65,8 @@ def main() -> int:
                     help="override the workload's cache layout: 0 contiguous, 16 paged")
     ap.add_argument("--kv-dtype", default="", choices=["", "bf16", "fp8"],
                     help="override the workload's cache dtype")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's request count")
+    ap.add_argument("--heads", default="", help="override head counts, e.g. 64/8")
     ap.add_argument("--fixed-len", type=int, default=0,
                     help="override the workload's length mix: every context this long")
     ap.add_argument("--event-every", type=int, default=8,
@@ -98,11 +100,14 @@ def main() -> int:
                           "copy_calibration_bytes_written": src.numel() * 4, "launches": 5}))
         return 0
     w = W.WORKLOADS[args.workload]
-    if args.block_size >= 0 or args.kv_dtype or args.fixed_len:
+    if args.block_size >= 0 or args.kv_dtype or args.fixed_len or args.batch or args.heads:
         import dataclasses
+        hq, hkv = ((int(x) for x in args.heads.split("/")) if args.heads
+                   else (w.num_q_heads, w.num_kv_heads))
         w = dataclasses.replace(
             w, block_size=w.block_size if args.block_size < 0 else args.block_size,
-            kv_dtype=args.kv_dtype or w.kv_dtype,
+            kv_dtype=args.kv_dtype or w.kv_dtype, batch=args.batch or w.batch,
+            num_q_heads=hq, num_kv_heads=hkv,
             len_recipe=("fixed", args.fixed_len) if args.fixed_len else w.len_recipe)
     t_gen = time.time()
     b = W.generate(w, threads=16)
@@ -179,8 +184,9 @@ def main() -> int:
     per_call_ms = (np.array([a.elapsed_time(bb) for a, bb in ev.values()]) if ev
                    else np.full(1, ms_per_step))
 
+    used_tokens = op.used_split_tokens() if op.num_splits > 1 else 0
     ab = W.algorithmic_bytes(w, lens, out_bytes=2 if args.out_dtype == "bf16" else 4,
-                             num_splits=op.num_splits)
+                             split_tokens=used_tokens)
     total_bytes = ab["total"]
     gbps = total_bytes / (ms_per_step * 1e-3) / 1e9
     kern_ms = float(per_call_ms.mean())
@@ -204,8 +210,10 @@ def main() -> int:
                    "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
                    "context": w.len_recipe, "kv_dtype": w.kv_dtype,
                    "layout": "paged16" if w.block_size else "contiguous",
-                   "out_dtype": args.out_dtype, "num_splits": op.num_splits,
-                   "split_tokens": op.split_tokens, "kv_buffers_rotated": copies},
+                   "out_dtype": args.out_dtype, "max_partitions": op.num_splits,
+                   "base_partition_tokens": op.split_tokens,
+                   "partition_tokens": used_tokens or op.split_tokens,
+                   "kv_buffers_rotated": copies},
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "attended_kv_tokens_per_s": round(ab["tokens"] / (ms_per_step * 1e-3), 1),
         "attended_head_tokens_per_s": round(ab["head_tokens"] / (ms_per_step * 1e-3), 1),

@@ -62,8 +62,10 @@ typedef struct {
     int32_t block_size;     /* 0: contiguous strided cache; 16: paged cache with a block table  */
     int32_t max_batch;      /* upper bound on `batch` of any call; sizes grid and workspace     */
     int32_t max_seq_len;    /* upper bound on any seq_lens[r]; sizes the split-KV partition     */
-    int32_t num_splits;     /* 0: library chooses; 1: never split; N>1: exactly N partitions of
-                               ceil(max_seq_len / N) tokens (rounded up to a multiple of 256)    */
+    int32_t num_splits;     /* 0: library chooses (a base partition size at creation, which the
+                               kernel may coarsen per call from seq_lens); 1: never split; N>1:
+                               exactly N partitions of ceil(max_seq_len / N) tokens (rounded up to
+                               a multiple of 256)                                                */
     float   softmax_scale;  /* 0 means 1/sqrt(head_dim)                                         */
     int32_t device;         /* HIP device ordinal the handle is bound to                        */
     int32_t kernel;         /* LAMINA_KERNEL_MFMA or LAMINA_KERNEL_VALU                         */
@@ -90,7 +92,7 @@ typedef struct {
 /*
  * Create a handle for one layer-share on cfg->device.  Validates cfg, picks the split-KV
  * partitioning and allocates the handle-owned workspace for partial results
- * ([max_batch][num_q_heads][splits][head_dim + 1] fp32; nothing when splits == 1).
+ * ([max_batch][num_q_heads][splits][head_dim + 1] fp32 plus 16 bytes; nothing when splits == 1).
  * On success *out_handle is set.  Errors: INVALID_ARG (NULL, non-positive sizes,
  * num_q_heads % num_kv_heads != 0, unknown dtype), UNSUPPORTED (head_dim != 128,
  * block_size not in {0, 16}, group size not in {1,2,4,8,16}), HIP, WORKSPACE.
@@ -149,10 +151,16 @@ const char *lamina_attn_last_error(lamina_attn_t h);
  * cfg is invalid.  Does not touch the GPU. */
 size_t lamina_attn_workspace_bytes(const lamina_attn_config *cfg);
 
-/* Partitioning chosen at creation: number of KV partitions per request (>= 1) and the
- * tokens per partition.  Used by callers that account for the partial-result traffic. */
+/* Partitioning chosen at creation: the largest number of KV partitions a request can have
+ * (>= 1; it sizes the workspace) and the base tokens per partition. */
 int lamina_attn_num_splits(lamina_attn_t h);
 int lamina_attn_split_tokens(lamina_attn_t h);
+
+/* Tokens per partition the most recent call on this handle actually used (the base size times
+ * 1, 2, 4, 8 or 16 when num_splits was 0).  For callers that account for the partial-result
+ * traffic.  Copies one int back from the device and therefore SYNCHRONISES; returns 0 before
+ * the first call, a negative error code if the copy fails. */
+int lamina_attn_used_split_tokens(lamina_attn_t h);
 
 /*
  * The two steps either side of the hot path on the attention device when the new token's

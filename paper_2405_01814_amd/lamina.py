@@ -27,7 +27,8 @@ LAMINA_KERNEL_MFMA, LAMINA_KERNEL_VALU = 0, 1
 
 EXPORTS = ("lamina_attn_create", "lamina_decode_attention", "lamina_attn_destroy",
            "lamina_attn_last_error", "lamina_attn_workspace_bytes", "lamina_attn_num_splits",
-           "lamina_attn_split_tokens", "lamina_append_kv", "lamina_fold_new_token")
+           "lamina_attn_split_tokens", "lamina_attn_used_split_tokens", "lamina_append_kv",
+           "lamina_fold_new_token")
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -91,6 +92,8 @@ def load():
     lib.lamina_attn_num_splits.argtypes = [vp]
     lib.lamina_attn_split_tokens.restype = ctypes.c_int
     lib.lamina_attn_split_tokens.argtypes = [vp]
+    lib.lamina_attn_used_split_tokens.restype = ctypes.c_int
+    lib.lamina_attn_used_split_tokens.argtypes = [vp]
     lib.lamina_append_kv.restype = ctypes.c_int
     lib.lamina_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(lamina_call_params)]
     lib.lamina_fold_new_token.restype = ctypes.c_int
@@ -168,6 +171,10 @@ class DecodeAttention:
         self.out_dtype = out_dtype
         self.num_splits = int(load().lamina_attn_num_splits(self.handle))
         self.split_tokens = int(load().lamina_attn_split_tokens(self.handle))
+
+    def used_split_tokens(self) -> int:
+        """Tokens per partition of the most recent call (synchronises the device)."""
+        return int(load().lamina_attn_used_split_tokens(self.handle))
 
     def close(self):
         if getattr(self, "handle", None) is not None:

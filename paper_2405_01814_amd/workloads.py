@@ -187,7 +187,7 @@ def generate(w: Workload, lens: np.ndarray | None = None, threads: int = 8,
     return out
 
 
-def algorithmic_bytes(w: Workload, lens, out_bytes: int = 4, num_splits: int = 1,
+def algorithmic_bytes(w: Workload, lens, out_bytes: int = 4, split_tokens: int = 0,
                       with_lse: bool = True) -> dict:
     """Bytes one call must move if every needed byte is touched exactly once.
 
@@ -195,7 +195,8 @@ def algorithmic_bytes(w: Workload, lens, out_bytes: int = 4, num_splits: int = 1
     once and shared by the G query heads of its group -- per token and layer that is
     the 2*e*(d/G) of the paper's capacity example (Sec. 2.2.2) for one layer.  The rest
     is the per-call operator I/O of Sec. 3.1 (q in, output out) plus the small index
-    arrays, and for split-KV the partial results written once and read once.
+    arrays, and for split-KV (split_tokens > 0: tokens per partition) the partial results
+    of every request that has more than one partition, written once and read once.
     """
     lens = np.asarray(lens, dtype=np.int64)
     R, Hq, Hkv, D = len(lens), w.num_q_heads, w.num_kv_heads, w.head_dim
@@ -208,7 +209,10 @@ def algorithmic_bytes(w: Workload, lens, out_bytes: int = 4, num_splits: int = 1
     if w.block_size:
         idx += int(((lens + w.block_size - 1) // w.block_size).sum()) * 4
     scales = 2 * R * Hkv * 4 if w.kv_dtype == "fp8" else 0
-    partials = 2 * R * Hq * num_splits * (D + 1) * 4 if num_splits > 1 else 0
+    partials = 0
+    if split_tokens > 0:
+        parts = (lens + split_tokens - 1) // split_tokens
+        partials = 2 * int(parts[parts > 1].sum()) * Hq * (D + 1) * 4
     total = kv + q + o + lse + idx + scales + partials
     return {"kv": kv, "q": q, "out": o, "lse": lse, "index": idx, "scales": scales,
             "partials": partials, "total": total,

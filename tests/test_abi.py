@@ -43,9 +43,9 @@ def good_cfg(**kw):
 
 def test_workspace_query_follows_the_partitioning():
     assert lamina.lamina_attn_workspace_bytes(good_cfg(num_splits=1)) == 0
-    assert lamina.lamina_attn_workspace_bytes(good_cfg(num_splits=8)) == 64 * 32 * 8 * 129 * 4
+    assert lamina.lamina_attn_workspace_bytes(good_cfg(num_splits=8)) == 64 * 32 * 8 * 129 * 4 + 16
     c = good_cfg(max_batch=16, max_seq_len=131072, num_splits=64)
-    assert lamina.lamina_attn_workspace_bytes(c) == 16 * 32 * 64 * 129 * 4
+    assert lamina.lamina_attn_workspace_bytes(c) == 16 * 32 * 64 * 129 * 4 + 16
     assert lamina.lamina_attn_workspace_bytes(good_cfg(head_dim=64)) == 0      # invalid cfg
 
 

@@ -419,3 +419,37 @@ def test_append_then_two_phase_equals_one_phase(name):
     torch.cuda.synchronize()
     assert torch.equal(before.view(iv), t["k"].view(iv))
     op.close()
+
+
+def test_partition_size_adapts_to_the_batch_and_is_reported():
+    d = dev()
+    w = W.WORKLOADS["llama3_8b_ctx4096"]
+    # small batch, long contexts: the base size (1024 tokens) stays
+    b = sized("llama3_8b_ctx4096", [8192, 6000])
+    op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=64, max_seq_len=8192)
+    assert (op.num_splits, op.split_tokens) == (8, 1024)
+    assert op.used_split_tokens() == 0                    # nothing has run yet
+    t = {k: v.to(d) for k, v in b.items() if isinstance(v, torch.Tensor)}
+    out, lse = op(t["q"], t["k"], t["v"], t["seq_lens"])
+    torch.cuda.synchronize()
+    assert op.used_split_tokens() == 1024
+    check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b), "bf16_f32")
+    # a big uniform batch on the same handle: partitions are coarsened, results still right
+    b = sized("llama3_8b_ctx4096", [8192] * 64)
+    t = {k: v.to(d) for k, v in b.items() if isinstance(v, torch.Tensor)}
+    out, lse = op(t["q"], t["k"], t["v"], t["seq_lens"])
+    torch.cuda.synchronize()
+    assert op.used_split_tokens() == 2048
+    pairs = sample_pairs(b, 40, 9)
+    check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b, pairs=pairs),
+          "bf16_f32", pairs=pairs)
+    op.close()
+    # an explicit partition count is never changed
+    op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=64, max_seq_len=8192,
+                                num_splits=16)
+    out, lse = op(t["q"], t["k"], t["v"], t["seq_lens"])
+    torch.cuda.synchronize()
+    assert (op.num_splits, op.split_tokens, op.used_split_tokens()) == (16, 512, 512)
+    check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b, pairs=pairs),
+          "bf16_f32", pairs=pairs)
+    op.close()

@@ -58,7 +58,7 @@ def test_named_workloads_have_the_stated_shapes():
     assert 1200 < np.median(l3) < 3200
     l4 = W.draw_lens(w["longctx_split64"])
     assert len(l4) == 16 and (l4 == 131072).all()
-    b4 = W.algorithmic_bytes(w["longctx_split64"], l4, num_splits=64)
+    b4 = W.algorithmic_bytes(w["longctx_split64"], l4, split_tokens=2048)
     assert b4["kv"] == 8192 * 2 ** 20 and b4["partials"] == 2 * 16 * 32 * 64 * 129 * 4
     assert w["llama_65b_mha_ctx4096"].group == 1 and w["llama_33b_mha_paged"].group == 1
     # 64 and 52 heads of 128 (d = 8192 and 6656) over 8 and 4 attention devices

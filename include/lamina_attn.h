@@ -42,10 +42,10 @@ enum {
 
 enum { LAMINA_BF16 = 0, LAMINA_FP8_E4M3 = 1, LAMINA_F32 = 2 };
 
-/* Kernel family used for the main pass.  Both compute the same function. */
+/* Kernel family of the main pass.  Only the matrix-core kernel exists; the field is kept so
+ * that a handle states which one it runs. */
 enum {
-    LAMINA_KERNEL_MFMA = 0,        /* default: matrix-core tiles for q.K^T and p.V          */
-    LAMINA_KERNEL_VALU = 1         /* plain vector-ALU kernel, kept for A/B measurements    */
+    LAMINA_KERNEL_MFMA = 0         /* matrix-core tiles for q.K^T and p.V                    */
 };
 
 /*
@@ -68,7 +68,7 @@ typedef struct {
                                a multiple of 256)                                                */
     float   softmax_scale;  /* 0 means 1/sqrt(head_dim)                                         */
     int32_t device;         /* HIP device ordinal the handle is bound to                        */
-    int32_t kernel;         /* LAMINA_KERNEL_MFMA or LAMINA_KERNEL_VALU                         */
+    int32_t kernel;         /* LAMINA_KERNEL_MFMA (0); anything else is rejected                */
 } lamina_attn_config;
 
 /*
@@ -95,7 +95,9 @@ typedef struct {
  * ([max_batch][num_q_heads][splits][head_dim + 1] fp32 plus 16 bytes; nothing when splits == 1).
  * On success *out_handle is set.  Errors: INVALID_ARG (NULL, non-positive sizes,
  * num_q_heads % num_kv_heads != 0, unknown dtype), UNSUPPORTED (head_dim != 128,
- * block_size not in {0, 16}, group size not in {1,2,4,8,16}), HIP, WORKSPACE.
+ * block_size not in {0, 16}, group size not in {1,2,4,8,16}; for handles that partition the
+ * KV range: max_batch > 1024, max_batch * num_kv_heads * num_splits > 65536, or a device
+ * with fewer than 128 compute units), HIP, WORKSPACE.
  */
 int lamina_attn_create(const lamina_attn_config *cfg, lamina_attn_t *out_handle);
 

@@ -23,7 +23,7 @@ LAMINA_ERR_UNSUPPORTED = -2
 LAMINA_ERR_HIP = -3
 LAMINA_ERR_WORKSPACE = -4
 LAMINA_BF16, LAMINA_FP8_E4M3, LAMINA_F32 = 0, 1, 2
-LAMINA_KERNEL_MFMA, LAMINA_KERNEL_VALU = 0, 1
+LAMINA_KERNEL_MFMA = 0
 
 EXPORTS = ("lamina_attn_create", "lamina_decode_attention", "lamina_attn_destroy",
            "lamina_attn_last_error", "lamina_attn_workspace_bytes", "lamina_attn_num_splits",

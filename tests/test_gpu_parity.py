@@ -453,3 +453,21 @@ def test_partition_size_adapts_to_the_batch_and_is_reported():
     check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b, pairs=pairs),
           "bf16_f32", pairs=pairs)
     op.close()
+
+
+def test_partitioned_handle_limits_are_reported_at_creation():
+    dev()
+    # unsplit handles take any batch; partitioned ones are limited by the LDS tables
+    op = lamina.DecodeAttention(8, 8, max_batch=5000, max_seq_len=2048)
+    assert op.num_splits == 1
+    op.close()
+    with pytest.raises(lamina.LaminaError) as ei:
+        lamina.DecodeAttention(8, 1, max_batch=2000, max_seq_len=100000)
+    assert ei.value.code == lamina.LAMINA_ERR_UNSUPPORTED
+    with pytest.raises(lamina.LaminaError) as ei:
+        lamina.DecodeAttention(8, 8, max_batch=1024, max_seq_len=8192, num_splits=16)
+    assert ei.value.code == lamina.LAMINA_ERR_UNSUPPORTED
+    # the library's own choice coarsens the base partition until the item budget holds
+    op = lamina.DecodeAttention(8, 8, max_batch=1024, max_seq_len=32768)
+    assert op.num_splits * 1024 * 8 <= 65536 and op.num_splits * op.split_tokens >= 32768
+    op.close()

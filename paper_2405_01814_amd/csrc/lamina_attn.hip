@@ -180,10 +180,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     constexpr int NSUB = TILE / 16;                       // 16-token MFMA sub-tiles per tile
     constexpr int NPAIR = NSUB / 2;                       // 32-token contraction steps for p.V
     constexpr int ROWB = FP8 ? 128 : 256;                 // bytes of one K or V row
-    constexpr int VSTRIDE = ROWB + (FP8 ? 16 : 32);       // LDS row pitch (bank spreading)
+    constexpr int VSTRIDE = ROWB + (FP8 ? 16 : 32);       // LDS row pitch of staged V (bank spreading)
+    constexpr int KSTRIDE = ROWB + 16;                    // LDS row pitch of staged K
     constexpr int KR = 8;                                 // 128-bit K loads per lane per tile
     constexpr int VR = 8;                                 // 128-bit V loads per lane per tile
-    constexpr int KPS = KR / NSUB;                        // K loads per sub-tile
     constexpr int LPR = ROWB / 16;                        // lanes that cover one V row
     constexpr int RPI = 64 / LPR;                         // V rows per load instruction
     constexpr int VBUF = TILE * VSTRIDE;                  // V staging bytes per wavefront
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     constexpr bool Q_AHEAD = !FP8 && GQ <= 2;
     constexpr int step = kWaves * TILE;                   // token stride between a wave's tiles
     constexpr int TRIP = kMaxGroup * kHeadDim + 2 * kMaxGroup;   // floats: O, then max, then sum
-    static_assert(VR * RPI == TILE && KR % NSUB == 0, "tile geometry");
+    static_assert(VR * RPI == TILE && KR == VR && KSTRIDE <= VSTRIDE, "tile geometry");
     __shared__ __attribute__((aligned(16))) unsigned char smem[kWaves * VBUF];
     __shared__ __attribute__((aligned(16))) float s_trip[kWaves * TRIP];   // end-of-item triples
     __shared__ int s_busy[kWaves];                        // 1 while s_trip[w] awaits the combine
@@ -392,16 +392,18 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                            int last, const int(&pg)[NSUB], u32x4(&kr)[KR], u32x4(&vr)[VR]) {
         // Addresses are a wave-uniform 64-bit base (request/head, or pool page) plus a 32-bit
         // per-lane byte offset, which keeps address arithmetic and registers small.
+        // K and V use the same lane mapping: an instruction covers whole rows (full 128-byte
+        // lines).  Partial-line accesses lose what the non-temporal hint gains.
 #pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) {
-            const int tok = min(ts + sub * 16 + col, last);
+        for (int i = 0; i < KR; ++i) {
+            const int tok = min(ts + i * RPI + lane / LPR, last);
+            const int sub = (i * RPI) / 16;               // compile-time per instruction
             const unsigned char *base =
                 PAGED ? kbase + (long long)pg[sub] * prm.pool_stride_block_b : kbase;
-            const unsigned off = PAGED ? (unsigned)((tok & 15) * ROWB + quad * 16)
-                                       : (unsigned)tok * (unsigned)prm.stride_tok_b + quad * 16;
-#pragma unroll
-            for (int s = 0; s < KPS; ++s)
-                kr[sub * KPS + s] = load_stream_128(base + off + s * 64);
+            const unsigned off = PAGED ? (unsigned)((tok & 15) * ROWB + (lane % LPR) * 16)
+                                       : (unsigned)tok * (unsigned)prm.stride_tok_b +
+                                             (lane % LPR) * 16;
+            kr[i] = load_stream_128(base + off);
         }
 #pragma unroll
         for (int i = 0; i < VR; ++i) {
@@ -467,13 +469,23 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
 
     // First half of a tile: everything that reads the tile's load registers.
     auto consume = [&](const u32x4(&kr)[KR], const u32x4(&vr)[VR], f32x4(&sc)[NSUB]) {
+        // K rows -> LDS (pitch KSTRIDE) -> MFMA A-operand layout (row = token col, the lane
+        // holds the 16-byte piece s*4 + quad of that row in k-step s).  The staging area is
+        // used for K first and for V afterwards; LDS operations of a wavefront execute in
+        // order, so V cannot overtake the K reads.
+#pragma unroll
+        for (int i = 0; i < KR; ++i) {
+            const int trow = i * RPI + lane / LPR;
+            *reinterpret_cast<u32x4 *>(vbuf + trow * KSTRIDE + (lane % LPR) * 16) = kr[i];
+        }
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            const unsigned char *krow = vbuf + (sub * 16 + col) * KSTRIDE + quad * 16;
             if (FP8) {
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2) {
-                    const u32x4 raw = kr[sub * 2 + s2];
+                    const u32x4 raw = *reinterpret_cast<const u32x4 *>(krow + s2 * 64);
                     const bf16x8 lo = join_bf16x4(fp8x4_to_bf16(raw[0]), fp8x4_to_bf16(raw[1]));
                     const bf16x8 hi = join_bf16x4(fp8x4_to_bf16(raw[2]), fp8x4_to_bf16(raw[3]));
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, qop[2 * s2], acc, 0, 0, 0);
@@ -482,7 +494,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             } else {
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
-                    const bf16x8 kop = __builtin_bit_cast(bf16x8, kr[sub * 4 + s]);
+                    const bf16x8 kop = *reinterpret_cast<const bf16x8 *>(krow + s * 64);
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qop[s], acc, 0, 0, 0);
                 }
             }

@@ -184,9 +184,9 @@ def main() -> int:
     per_call_ms = (np.array([a.elapsed_time(bb) for a, bb in ev.values()]) if ev
                    else np.full(1, ms_per_step))
 
-    used_tokens = op.used_split_tokens() if op.num_splits > 1 else 0
+    n_partials = op.count_partials(lens)
     ab = W.algorithmic_bytes(w, lens, out_bytes=2 if args.out_dtype == "bf16" else 4,
-                             split_tokens=used_tokens)
+                             partial_results=n_partials)
     total_bytes = ab["total"]
     gbps = total_bytes / (ms_per_step * 1e-3) / 1e9
     kern_ms = float(per_call_ms.mean())
@@ -210,9 +210,10 @@ def main() -> int:
                    "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
                    "context": w.len_recipe, "kv_dtype": w.kv_dtype,
                    "layout": "paged16" if w.block_size else "contiguous",
-                   "out_dtype": args.out_dtype, "max_partitions": op.num_splits,
-                   "base_partition_tokens": op.split_tokens,
-                   "partition_tokens": used_tokens or op.split_tokens,
+                   "out_dtype": args.out_dtype,
+                   "split_kv": {1: "none", 0: "balanced"}.get(op.num_splits, "fixed"),
+                   "partitions": op.num_splits, "partition_tokens": op.split_tokens,
+                   "partial_results": n_partials,
                    "kv_buffers_rotated": copies},
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "attended_kv_tokens_per_s": round(ab["tokens"] / (ms_per_step * 1e-3), 1),
@@ -223,7 +224,7 @@ def main() -> int:
                      "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": traffic,
                      "kernel": "decode_mfma_kernel" + (" + merge_partials_kernel"
-                                                       if op.num_splits > 1 else ""),
+                                                       if op.num_splits != 1 else ""),
                      "launches_timed": int(len(per_call_ms)),
                      "launch_ms_mean": round(kern_ms, 5),
                      "launch_ms_median": round(float(np.median(per_call_ms)), 5),

@@ -62,10 +62,12 @@ typedef struct {
     int32_t block_size;     /* 0: contiguous strided cache; 16: paged cache with a block table  */
     int32_t max_batch;      /* upper bound on `batch` of any call; sizes grid and workspace     */
     int32_t max_seq_len;    /* upper bound on any seq_lens[r]; sizes the split-KV partition     */
-    int32_t num_splits;     /* 0: library chooses (a base partition size at creation, which the
-                               kernel may coarsen per call from seq_lens); 1: never split; N>1:
-                               exactly N partitions of ceil(max_seq_len / N) tokens (rounded up to
-                               a multiple of 256)                                                */
+    int32_t num_splits;     /* how the KV range of a (request, kv head) row is cut (split-KV):
+                               1: never; N>1: into N partitions of ceil(max_seq_len / N) tokens
+                               (rounded up to a multiple of 256), each processed on its own;
+                               0: the library decides, normally "balanced": per call, from seq_lens,
+                               every work-group gets the same share of the call's tokens and a row
+                               is cut only where one share ends and the next begins              */
     float   softmax_scale;  /* 0 means 1/sqrt(head_dim)                                         */
     int32_t device;         /* HIP device ordinal the handle is bound to                        */
     int32_t kernel;         /* LAMINA_KERNEL_MFMA (0); anything else is rejected                */
@@ -90,14 +92,14 @@ typedef struct {
 } lamina_call_params;
 
 /*
- * Create a handle for one layer-share on cfg->device.  Validates cfg, picks the split-KV
- * partitioning and allocates the handle-owned workspace for partial results
- * ([max_batch][num_q_heads][splits][head_dim + 1] fp32 plus 16 bytes; nothing when splits == 1).
+ * Create a handle for one layer-share on cfg->device.  Validates cfg, picks the partitioning
+ * and allocates the handle-owned workspace for partial results (see
+ * lamina_attn_workspace_bytes; nothing when rows are never cut).
  * On success *out_handle is set.  Errors: INVALID_ARG (NULL, non-positive sizes,
  * num_q_heads % num_kv_heads != 0, unknown dtype), UNSUPPORTED (head_dim != 128,
- * block_size not in {0, 16}, group size not in {1,2,4,8,16}; for handles that partition the
- * KV range: max_batch > 1024, max_batch * num_kv_heads * num_splits > 65536, or a device
- * with fewer than 128 compute units), HIP, WORKSPACE.
+ * block_size not in {0, 16}, group size not in {1,2,4,8,16}, num_splits > 1 with
+ * max_batch > 1024, max_batch * num_kv_heads * partitions per row above 2^30), HIP, WORKSPACE.
+ * With num_splits == 0 and max_batch > 1024 rows are never cut.
  */
 int lamina_attn_create(const lamina_attn_config *cfg, lamina_attn_t *out_handle);
 
@@ -149,20 +151,25 @@ int lamina_attn_destroy(lamina_attn_t h);
  * lamina_attn_create on this thread).  Owned by the library; valid until the next call. */
 const char *lamina_attn_last_error(lamina_attn_t h);
 
-/* Bytes of device workspace a handle made from cfg would own (0 when unsplit), or 0 if
- * cfg is invalid.  Does not touch the GPU. */
+/* Bytes of device workspace a handle made from cfg would own, or 0 if cfg is invalid or rows are
+ * never cut.  It holds one partial result (G x (head_dim + 1) fp32) per piece a call can produce
+ * -- max_batch * num_kv_heads * N pieces for fixed partitions, max_batch * num_kv_heads + 1024
+ * for balanced shares -- plus max_batch + 1 int32 prefix sums.  Does not touch the GPU. */
 size_t lamina_attn_workspace_bytes(const lamina_attn_config *cfg);
 
-/* Partitioning chosen at creation: the largest number of KV partitions a request can have
- * (>= 1; it sizes the workspace) and the base tokens per partition. */
+/* Partitioning chosen at creation.  lamina_attn_num_splits: 1 = rows are never cut, N > 1 = fixed
+ * partitions, 0 = balanced shares decided per call.  lamina_attn_split_tokens: tokens per fixed
+ * partition, or the granularity of balanced shares (128 tokens for bf16, 256 for fp8 caches), or
+ * 0 when rows are never cut. */
 int lamina_attn_num_splits(lamina_attn_t h);
 int lamina_attn_split_tokens(lamina_attn_t h);
 
-/* Tokens per partition the most recent call on this handle actually used (the base size times
- * 1, 2, 4, 8 or 16 when num_splits was 0).  For callers that account for the partial-result
- * traffic.  Copies one int back from the device and therefore SYNCHRONISES; returns 0 before
- * the first call, a negative error code if the copy fails. */
-int lamina_attn_used_split_tokens(lamina_attn_t h);
+/* Number of per-query-head partial results ((head_dim + 1) fp32 each, written once by the main
+ * pass and read once by the merge) that a call with these lengths produces on this handle: rows
+ * that are not cut produce none.  For callers that account for the operator's memory traffic.
+ * host_seq_lens is a HOST array of `batch` lengths; nothing touches the GPU.  Returns a negative
+ * error code for a NULL argument or batch outside [0, max_batch]. */
+int64_t lamina_attn_count_partials(lamina_attn_t h, const int32_t *host_seq_lens, int32_t batch);
 
 /*
  * The two steps either side of the hot path on the attention device when the new token's

@@ -45,9 +45,12 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kChunkAlign = 256;       // partition sizes are multiples of 4 wavefronts x 64 tokens
 constexpr int kMaxGroup = 16;          // query heads per kv head the MFMA tile can hold
 constexpr int kMaxSplitBatch = 1024;   // requests per call when the KV range is partitioned
-constexpr int kTableSlots = 256;       // work items one work-group can be dealt per call
-constexpr int kCoarsenSteps = 4;       // the kernel may double the base partition size this often
-constexpr int kItemsPerGroup = 4;      // ... while an item stays below 1/4 of a work-group's share
+// How the KV range of a (request, kv head) row is cut into the pieces work-groups process.
+enum : int {
+    kModeRows = 0,                     // never cut: a piece is a whole row
+    kModeFixed = 1,                    // fixed partitions of `unit` tokens, each its own piece
+    kModeBalanced = 2                  // equal shares of the call's tokens per work-group
+};
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -59,17 +62,18 @@ struct MainParams {
     const int32_t *block_table;
     void *out;
     float *lse;
-    float *part_out;                   // [R][Hq][P][128], normalised partial outputs
-    float *part_lse;                   // [R][Hq][P], natural-log partial denominators
+    float *part_out;                   // [piece][G][128], normalised partial outputs
+    float *part_lse;                   // [piece][G], natural-log partial denominators
+    int *cum;                          // [R + 1]: units before request r, written by the main pass
     const float *k_scale;
     const float *v_scale;
     long long stride_req_b, stride_head_b, stride_tok_b;     // bytes (contiguous mode)
     long long pool_stride_block_b, pool_stride_head_b;       // bytes (paged mode)
     int bt_stride;
     int Hq, Hkv, G;
-    int P, chunk;                      // partitions per request at most, base partition size
-    int adapt;                         // 1: the kernel may coarsen the partition size
-    int *chunk_used;                   // device scalar: partition size the kernel settled on
+    int mode;                          // kModeRows / kModeFixed / kModeBalanced
+    int P;                             // kModeFixed: partitions per row at most
+    int unit;                          // tokens per unit (split modes)
     int batch;
     int out_is_bf16;
     float scale_log2;                  // softmax scale times log2(e)
@@ -81,11 +85,31 @@ struct MergeParams {
     const int32_t *seq_lens;
     void *out;
     float *lse;
-    int Hq, P;
-    const int *chunk_used;             // partition size the main pass settled on
-    int rows;
+    const int *cum;                    // [R + 1], units before request r (from the main pass)
+    int Hq, Hkv, G;
+    int mode;                          // kModeFixed or kModeBalanced
+    int nwg;                           // work-groups of the main pass
+    int R;
+    int rows;                          // R * Hq
     int out_is_bf16;
 };
+
+// Balanced mode deals U units to nwg work-groups as evenly as whole units allow: the first
+// U % nwg work-groups take U / nwg + 1 units, the others U / nwg; work-group j starts at unit
+// j * (U / nwg) + min(j, U % nwg).  These two helpers are that rule and its inverse; the main
+// pass, the merge and the host-side accounting all use them.
+__host__ __device__ inline long long share_begin(long long U, int nwg, int j)
+{
+    const long long q = U / nwg, rem = U % nwg;
+    return j * q + (j < rem ? j : rem);
+}
+__host__ __device__ inline int share_owner(long long U, int nwg, long long u)
+{
+    const long long q = U / nwg, rem = U % nwg;
+    if (u < rem * (q + 1))
+        return (int)(u / (q + 1));
+    return (int)(rem + (u - rem * (q + 1)) / q);          // q >= 1 here: u >= rem * (q + 1)
+}
 
 __device__ __forceinline__ u32x4 load_stream_128(const unsigned char *p)
 {
@@ -140,21 +164,28 @@ __device__ __forceinline__ void store_out(void *out, int out_is_bf16, size_t idx
 
 // -------------------------------------------------------------------------------------------
 // Main pass: a persistent kernel.  The grid is a fixed number of work-groups (two per compute
-// unit) that stay resident and share out a compact list of work items.
+// unit) that stay resident and share out the call's work among themselves.
 //
-// Work items.  Request r is cut into n(r) = max(1, ceil(seq_lens[r] / chunk)) partitions of
-// `chunk` tokens (one partition when the handle is unsplit); an item is (partition, kv head).
-// Items are numbered with the kv head fastest and requests in order, skipping nothing but
-// the partitions a request is too short to have; work-group j takes items j, j + grid,
-// j + 2 grid, ...  Every work-group derives the numbering itself from seq_lens (a prefix sum
-// and a table of its own items in LDS), so the host never reads seq_lens and no planning
-// kernel runs.  Equal-sized items dealt round-robin keep skewed batches balanced.
+// Work.  The rows (request r, kv head g), g fastest, are laid end to end as a stream of UNITS:
+// row (r, g) holds n(r) units, where
+//   rows mode       n = 1 (the row is never cut),
+//   fixed mode      n = number of `unit`-token partitions of seq_lens[r] (at least one),
+//   balanced mode   n = number of 128-token (bf16) / 256-token (fp8) blocks (at least one).
+// Work-group j takes a contiguous range of units, all ranges equal to within one unit.  In
+// rows and fixed mode every unit is one ITEM; in balanced mode an item is the part of one row
+// that falls into the work-group's range, however long -- so every work-group streams the same
+// number of tokens whatever the mix of lengths, and a row is cut only where a range ends
+// (at most one extra partial result per work-group).  Every work-group derives its range
+// itself from seq_lens (a prefix sum in LDS), so the host never reads seq_lens and no
+// planning kernel runs.
 //
 // Inside an item the four wavefronts take 32-token (bf16) or 64-token (fp8) tiles
 // w, w+4, w+8, ... and never synchronise until the item ends, where they combine their
 // (max, denominator, output) triples through LDS -- the same identity as the cross-partition
-// merge.  A request with a single partition is written straight to out/lse; otherwise the
-// item writes the partial pair (A_q(I), ln S_q(I)) of Sec. 4.2.2 to the workspace.
+// merge.  An item that covers its whole row is written straight to out/lse; otherwise the
+// item writes the partial pair (A_q(I), ln S_q(I)) of Sec. 4.2.2 to the workspace, at piece
+// index `unit number` (fixed mode) or `row number + work-group number` (balanced mode; both
+// grow along the stream and one of them changes between consecutive items).
 //
 // Streaming.  Each wavefront keeps two register sets of 16 KiB of K+V in flight and refills a
 // set as soon as its registers have been read.  When an item runs out of tiles the refills
@@ -199,10 +230,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     __shared__ __attribute__((aligned(16))) float s_trip[kWaves * TRIP];   // end-of-item triples
     __shared__ int s_busy[kWaves];                        // 1 while s_trip[w] awaits the combine
     __shared__ int s_count;                               // wavefronts that finished the item
-    __shared__ int s_cum[kMaxSplitBatch + 1];             // partitions before request r
-    __shared__ int s_tab_r[kTableSlots];                  // this work-group's items: request
-    __shared__ int s_tab_c[kTableSlots];                  //                          partition
-    __shared__ int s_tab_len[kTableSlots];                //                          seq_lens[request]
+    __shared__ int s_cum[kMaxSplitBatch + 1];             // units before request r (split modes)
     __shared__ float s_wgt[kWaves * kMaxGroup];           // combine weights of the four triples
     __shared__ int s_wsum[kWaves];
 
@@ -213,15 +241,19 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     const int quad = lane >> 4;
     const int G = prm.G;
     const int R = prm.batch;
-    int C = prm.chunk;
     const int Hkv = prm.Hkv;
-    const bool split = prm.P > 1;
+    const int mode = prm.mode;
+    const int unit = prm.unit;
     const int j = blockIdx.x;
     const int nwg = gridDim.x;
     const const_i32_ptr lens = (const_i32_ptr)prm.seq_lens;
 
-    auto nparts = [&](int len) { return min(prm.P, max(1, (len + C - 1) / C)); };
-    unsigned char *vbuf = smem + w * VBUF;                // this wavefront's V staging area
+    // units of one row of a request with `len` tokens (split modes)
+    auto units_of = [&](int len) {
+        const int n = max(1, (len + unit - 1) / unit);
+        return mode == kModeFixed ? min(prm.P, n) : n;
+    };
+    unsigned char *vbuf = smem + w * VBUF;                // this wavefront's staging area
 
     if (tid < kWaves)
         s_busy[tid] = 0;
@@ -229,45 +261,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         s_count = 0;
     __syncthreads();
 
-    // ---- the work list ---------------------------------------------------------------------
-    int total_items;
-    if (split) {
+    // ---- this work-group's range of units --------------------------------------------------
+    long long U;                                          // units in the call
+    if (mode != kModeRows) {
         const int per = (R + kThreads - 1) / kThreads;
         const int b = tid * per;
         const int e = min(R, b + per);
-        if (prm.adapt) {
-            // Partition size for THIS batch: the base size doubled as often as keeps an item
-            // below a quarter of a work-group's average share of the batch's tokens.  Few,
-            // long items waste nothing at item boundaries; many, short ones are what balances
-            // skewed or small batches.  Every work-group takes the same decision from the
-            // same seq_lens.
-            int toks = 0;
-            for (int i = b; i < e; ++i)
-                toks += prm.seq_lens[i];
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1)
-                toks += __shfl_xor(toks, off);
-            if (lane == 0)
-                s_wsum[w] = toks;
-            __syncthreads();
-            long long total = 0;
-#pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww)
-                total += s_wsum[ww];
-            __syncthreads();                              // s_wsum is reused by the scan below
-            const long long share = total * Hkv / nwg;    // tokens per work-group
-            int pick = 0;
-#pragma unroll
-            for (int k = 1; k <= kCoarsenSteps; ++k)
-                if ((long long)(C << k) * kItemsPerGroup <= share)
-                    pick = k;
-            C <<= __builtin_amdgcn_readfirstlane(pick);
-        }
-        if (j == 0 && tid == 0)
-            *prm.chunk_used = C;
         int sum = 0;
         for (int i = b; i < e; ++i)
-            sum += nparts(prm.seq_lens[i]);
+            sum += units_of(prm.seq_lens[i]);
         int inc = sum;                                    // inclusive scan inside the wavefront
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -288,39 +290,94 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         int run = wbase + inc - sum;
         for (int i = b; i < e; ++i) {
             s_cum[i] = run;
-            run += nparts(prm.seq_lens[i]);
+            if (j == 0)
+                prm.cum[i] = run;                         // the merge pass reads it back
+            run += units_of(prm.seq_lens[i]);
         }
-        if (tid == 0)
+        if (tid == 0) {
             s_cum[R] = tot;
-        __syncthreads();
-        total_items = __builtin_amdgcn_readfirstlane(tot) * Hkv;
-    } else {
-        total_items = R * Hkv;
-    }
-    const int nslots = (j < total_items) ? (total_items - j + nwg - 1) / nwg : 0;
-    if (nslots == 0)
-        return;
-    if (split) {
-        for (int sl = tid; sl < nslots; sl += kThreads) {  // nslots <= kTableSlots (host check)
-            const int cidx = (j + sl * nwg) / Hkv;
-            int lo = 0, hi = R;                           // largest r with cum[r] <= cidx
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (s_cum[mid] <= cidx)
-                    lo = mid;
-                else
-                    hi = mid;
-            }
-            s_tab_r[sl] = lo;
-            s_tab_c[sl] = cidx - s_cum[lo];
-            s_tab_len[sl] = prm.seq_lens[lo];
+            if (j == 0)
+                prm.cum[R] = tot;
         }
         __syncthreads();
+        U = (long long)__builtin_amdgcn_readfirstlane(tot) * Hkv;
+    } else {
+        U = (long long)R * Hkv;
     }
+    const int u0 = (int)share_begin(U, nwg, j);
+    const int u1 = (int)share_begin(U, nwg, j + 1);
+    if (u0 >= u1)
+        return;
+
+    // Walking the stream: the next unit to hand out and the row it lies in (all wave-uniform).
+    struct Walk {
+        int u;                        // next unit
+        int r, g;                     // its row
+        int S, n;                     // the row's first unit and number of units
+        int len;                      // seq_lens[r]
+    };
+    auto load_row = [&](Walk &s) {
+        s.len = lens[s.r];
+        if (mode == kModeRows) {
+            s.n = 1;
+            s.S = s.r * Hkv + s.g;
+        } else {
+            const int c0 = __builtin_amdgcn_readfirstlane(s_cum[s.r]);
+            const int c1 = __builtin_amdgcn_readfirstlane(s_cum[s.r + 1]);
+            s.n = c1 - c0;
+            s.S = Hkv * c0 + s.g * s.n;
+        }
+    };
+    struct Piece {
+        int r, g;
+        int t0, t1;                   // token range
+        int whole;                    // covers its whole row: result goes straight to out/lse
+        int dest;                     // piece index in the workspace otherwise
+    };
+    // Hand out the item that starts at unit s.u (the caller has checked s.u < u1).
+    auto next_piece = [&](Walk &s, Piece &p) {
+        const int E = s.S + s.n;
+        const int pe = (mode == kModeBalanced) ? min(E, u1) : s.u + 1;
+        p.r = s.r;
+        p.g = s.g;
+        p.t0 = (s.u - s.S) * unit;
+        p.t1 = (mode == kModeRows) ? s.len : min(s.len, (pe - s.S) * unit);
+        p.whole = (s.u == s.S) && (pe == E);
+        p.dest = (mode == kModeBalanced) ? s.r * Hkv + s.g + j : s.u;
+        s.u = pe;
+        if (pe == E) {
+            if (++s.g == Hkv) {
+                s.g = 0;
+                ++s.r;
+            }
+            if (pe < u1)
+                load_row(s);
+        }
+    };
+    Walk start;
+    start.u = u0;
+    if (mode == kModeRows) {
+        start.r = u0 / Hkv;
+        start.g = u0 % Hkv;
+    } else {
+        int lo = 0, hi = R;                               // largest r with Hkv * cum[r] <= u0
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if ((long long)Hkv * s_cum[mid] <= u0)
+                lo = mid;
+            else
+                hi = mid;
+        }
+        start.r = __builtin_amdgcn_readfirstlane(lo);
+        const int c0 = __builtin_amdgcn_readfirstlane(s_cum[start.r]);
+        const int c1 = __builtin_amdgcn_readfirstlane(s_cum[start.r + 1]);
+        start.g = (u0 - Hkv * c0) / (c1 - c0);
+    }
+    load_row(start);
 
     // Wave-uniform description of the tiles one wavefront owns in one item.
     struct Desc {
-        int slot;                     // -1: none
+        int slot;                     // ordinal of the item in this work-group; -1: none
         int r, g;
         int t0w;                      // first token of this wavefront's first tile
         int t1;                       // end of the item's token range
@@ -329,47 +386,36 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         const unsigned char *vbase;
         const_i32_ptr bt;
     };
-    auto identify = [&](int slot, int &r, int &g, int &c, int &len) {
-        const int it = j + slot * nwg;
-        g = it % Hkv;
-        if (split) {
-            r = __builtin_amdgcn_readfirstlane(s_tab_r[slot]);
-            c = __builtin_amdgcn_readfirstlane(s_tab_c[slot]);
-            len = __builtin_amdgcn_readfirstlane(s_tab_len[slot]);
-        } else {
-            r = it / Hkv;
-            c = 0;
-            len = lens[r];
-        }
-    };
-    auto describe = [&](int slot, Desc &d) {
-        int r, g, c, len;
-        identify(slot, r, g, c, len);
+    auto describe = [&](const Piece &p, int slot, Desc &d) {
         d.slot = slot;
-        d.r = r;
-        d.g = g;
-        d.t0w = c * C + w * TILE;
-        d.t1 = min(len, c * C + C);
+        d.r = p.r;
+        d.g = p.g;
+        d.t0w = p.t0 + w * TILE;
+        d.t1 = p.t1;
         const int nt = (d.t0w < d.t1) ? (d.t1 - d.t0w + step - 1) / step : 0;
         d.n_even = (nt + 1) & ~1;
         if (PAGED) {
-            d.kbase = prm.k + (long long)g * prm.pool_stride_head_b;
-            d.vbase = prm.v + (long long)g * prm.pool_stride_head_b;
-            d.bt = (const_i32_ptr)(prm.block_table + (size_t)r * prm.bt_stride);
+            d.kbase = prm.k + (long long)p.g * prm.pool_stride_head_b;
+            d.vbase = prm.v + (long long)p.g * prm.pool_stride_head_b;
+            d.bt = (const_i32_ptr)(prm.block_table + (size_t)p.r * prm.bt_stride);
         } else {
             const long long off =
-                (long long)r * prm.stride_req_b + (long long)g * prm.stride_head_b;
+                (long long)p.r * prm.stride_req_b + (long long)p.g * prm.stride_head_b;
             d.kbase = prm.k + off;
             d.vbase = prm.v + off;
             d.bt = nullptr;
         }
     };
-    // First item at or after `from` in which this wavefront has at least one tile.
-    auto find_next = [&](int from, Desc &d) {
+    // Next item, from the look-ahead position on, in which this wavefront has at least one tile.
+    Walk look = start;
+    int look_slot = 0;
+    auto find_next = [&](Desc &d) {
         d.slot = -1;
-        for (int sl = from; sl < nslots; ++sl) {
+        while (look.u < u1) {
+            Piece p;
+            next_piece(look, p);
             Desc t;
-            describe(sl, t);
+            describe(p, look_slot++, t);
             if (t.n_even > 0) {
                 d = t;
                 return;
@@ -585,7 +631,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     // item; whichever of the four arrives last combines the triples (same identity as the
     // cross-partition merge) and writes the item's result.  A wavefront can be at most one
     // item ahead: it may not overwrite its parked triple before that item was combined.
-    auto finalize = [&](int slot) {
+    auto finalize = [&](const Piece &id) {
         l_run += __shfl_xor(l_run, 16);
         l_run += __shfl_xor(l_run, 32);
         {
@@ -624,9 +670,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         if (arrived != kWaves - 1)
             return;
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-        int r, g, c, len;
-        identify(slot, r, g, c, len);
-        const bool whole = nparts(len) == 1;              // the request has no other partition
+        const int r = id.r, g = id.g;
+        const bool whole = id.whole != 0;                 // the row has no other piece
         float vs = 1.0f;
         if (FP8)
             vs = ((const __attribute__((address_space(4))) float *)prm.v_scale)[(size_t)r * Hkv + g];
@@ -649,7 +694,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                     if (prm.lse)
                         prm.lse[row] = lse_nat;
                 } else {
-                    prm.part_lse[row * prm.P + c] = lse_nat;
+                    prm.part_lse[(size_t)id.dest * G + col] = lse_nat;
                 }
             }
         }
@@ -668,7 +713,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                 }
                 const size_t row = (size_t)r * prm.Hq + g * G + h;
                 if (!whole) {
-                    *reinterpret_cast<f32x4 *>(prm.part_out + (row * prm.P + c) * kHeadDim + d4) = o;
+                    *reinterpret_cast<f32x4 *>(prm.part_out + ((size_t)id.dest * G + h) * kHeadDim + d4) = o;
                 } else if (prm.out_is_bf16) {
                     u32x2 pk;
                     pk[0] = (unsigned)bf16_bits(o[0]) | ((unsigned)bf16_bits(o[1]) << 16);
@@ -694,7 +739,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     u32x4 qn[GQ];                   // Q rows of the wavefront's next item, requested an item ahead
     float cn = 0.0f;
     Desc nxt;
-    find_next(0, nxt);
+    find_next(nxt);
     if (nxt.slot >= 0) {
         // prologue: the first two tile slots of this wavefront's first item, and its Q
         fetch_pages(nxt.bt, nxt.t0w, nxt.t1 - 1, pg);
@@ -708,7 +753,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         cn = score_scale(nxt.r, nxt.g);
         wait_vmem_all();                                  // start-up only: nothing else to do yet
     }
-    for (int slot = 0; slot < nslots; ++slot) {
+    Walk at = start;                // the item every wavefront of the work-group is on
+    for (int slot = 0; at.u < u1; ++slot) {
+        Piece id;
+        next_piece(at, id);
         if (nxt.slot == slot) {
             // Sets A and B already hold (or are receiving) this item's first two tile slots.
             const Desc cur = nxt;
@@ -719,7 +767,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                 wait_vmem_all();                          // also keeps the tile loop's waits exact
             }
             install_q(qn);
-            find_next(slot + 1, nxt);
+            find_next(nxt);
             // Where refills go once this item's tiles are exhausted: the next item's first
             // two slots, or -- at the very end -- harmless reloads of this item's last row.
             const bool more = nxt.slot >= 0;
@@ -772,18 +820,19 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                 ts += 2 * step;
             }
         }
-        finalize(slot);
+        finalize(id);
     }
 }
 
 // -------------------------------------------------------------------------------------------
-// Cross-partition merge (Sec. 4.2.2 identity, P parts, log-sum-exp form):
+// Cross-partition merge (Sec. 4.2.2 identity, any number of parts, log-sum-exp form):
 //   lse = ln sum_p e^{lse_p},  out = sum_p e^{lse_p - lse} out_p.
-// One wavefront per (request, query head) row, four rows per work-group; lane d owns output
-// columns 2d and 2d+1.  Lane p first holds partition p's weight (the log-sum-exp reduction is
-// two wave reductions), then all lanes stream the partial outputs with independent loads.
-// Only the first ceil(len / chunk) partitions were written by the main pass, and a request
-// with a single partition was already written to out/lse by the main pass.
+// One wavefront per (request, query head) row, four rows per work-group.  Which pieces a row
+// was cut into follows from the unit prefix sums the main pass left in the workspace and the
+// dealing rule; a row that was never cut was already written to out/lse by the main pass.
+// Lane p first holds piece p's weight (the log-sum-exp reduction is two wave reductions);
+// then the two half-waves take alternate pieces, each lane four output columns, sixteen
+// independent loads in flight per step.
 // -------------------------------------------------------------------------------------------
 constexpr int kMergeRowsPerBlock = 4;
 
@@ -794,46 +843,72 @@ __global__ __launch_bounds__(64 * kMergeRowsPerBlock) void merge_partials_kernel
     if (row >= prm.rows)
         return;
     const int r = row / prm.Hq;
-    const int len = prm.seq_lens[r];
-    const int chunk = *prm.chunk_used;
-    const int np = min(prm.P, max(1, (len + chunk - 1) / chunk));
+    const int hq = row - r * prm.Hq;
+    const int g = hq / prm.G;
+    const int hl = hq - g * prm.G;
+    const int c0 = prm.cum[r];
+    const int n = prm.cum[r + 1] - c0;
+    const long long S = (long long)prm.Hkv * c0 + (long long)g * n;   // the row's first unit
+    long long first;
+    int np;
+    if (prm.mode == kModeFixed) {
+        first = S;
+        np = n;
+    } else {
+        const long long U = (long long)prm.Hkv * prm.cum[prm.R];
+        const int wf = share_owner(U, prm.nwg, S);
+        np = share_owner(U, prm.nwg, S + n - 1) - wf + 1;
+        first = (long long)r * prm.Hkv + g + wf;
+    }
     if (np == 1)
         return;                                           // the main pass wrote this row itself
-    const float *pl = prm.part_lse + (size_t)row * prm.P;
-    const float *po = prm.part_out + (size_t)row * prm.P * kHeadDim;
+    const size_t pstride = (size_t)prm.G;
+    const float *pl = prm.part_lse + (size_t)first * prm.G + hl;
+    const float *po = prm.part_out + ((size_t)first * prm.G + hl) * kHeadDim;
     float M = -INFINITY;
     for (int p0 = 0; p0 < np; p0 += 64) {
-        const float v = (p0 + lane < np) ? pl[p0 + lane] : -INFINITY;
+        const float v = (p0 + lane < np) ? pl[(size_t)(p0 + lane) * pstride] : -INFINITY;
         M = fmaxf(M, v);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1)
         M = fmaxf(M, __shfl_xor(M, off));
+    const int half = lane >> 5;
+    const int c4 = (lane & 31) * 4;
     float W = 0.0f;
-    float o0 = 0.0f, o1 = 0.0f;
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
     for (int p0 = 0; p0 < np; p0 += 64) {
-        const float e = (p0 + lane < np) ? __expf(pl[p0 + lane] - M) : 0.0f;
+        const float e = (p0 + lane < np) ? __expf(pl[(size_t)(p0 + lane) * pstride] - M) : 0.0f;
         W += e;
         const int cnt = min(64, np - p0);
-#pragma unroll 4
-        for (int p = 0; p < cnt; ++p) {
-            const float w = __shfl(e, p);
-            const float2 t = *reinterpret_cast<const float2 *>(po + (size_t)(p0 + p) * kHeadDim +
-                                                              2 * lane);
-            o0 += w * t.x;
-            o1 += w * t.y;
+#pragma unroll 8
+        for (int i = 0; i < (cnt + 1) / 2; ++i) {         // same trip count in both half-waves
+            const int p = 2 * i + half;
+            const int pc = min(p, cnt - 1);
+            float wgt = __shfl(e, pc);
+            wgt = (p < cnt) ? wgt : 0.0f;
+            const f32x4 t = *reinterpret_cast<const f32x4 *>(
+                po + (size_t)(p0 + pc) * pstride * kHeadDim + c4);
+            o += wgt * t;
         }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1)
         W += __shfl_xor(W, off);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        o[i] += __shfl_xor(o[i], 32);
     const float inv = 1.0f / W;
-    const size_t at = (size_t)row * kHeadDim + 2 * lane;
-    if (prm.out_is_bf16) {
-        static_cast<unsigned *>(prm.out)[at >> 1] =
-            (unsigned)bf16_bits(o0 * inv) | ((unsigned)bf16_bits(o1 * inv) << 16);
-    } else {
-        *reinterpret_cast<float2 *>(static_cast<float *>(prm.out) + at) = make_float2(o0 * inv, o1 * inv);
+    if (half == 0) {
+        const size_t at = (size_t)row * kHeadDim + c4;
+        if (prm.out_is_bf16) {
+            u32x2 pk;
+            pk[0] = (unsigned)bf16_bits(o[0] * inv) | ((unsigned)bf16_bits(o[1] * inv) << 16);
+            pk[1] = (unsigned)bf16_bits(o[2] * inv) | ((unsigned)bf16_bits(o[3] * inv) << 16);
+            *reinterpret_cast<u32x2 *>(static_cast<unsigned short *>(prm.out) + at) = pk;
+        } else {
+            *reinterpret_cast<f32x4 *>(static_cast<float *>(prm.out) + at) = o * inv;
+        }
     }
     if (lane == 0 && prm.lse)
         prm.lse[row] = M + logf(W);
@@ -980,10 +1055,12 @@ __global__ __launch_bounds__(256) void fold_new_token_kernel(const NewTokenParam
 struct lamina_attn {
     lamina_attn_config cfg;
     int group;
-    int num_splits;
-    int split_tokens;
+    int mode;                    // kModeRows / kModeFixed / kModeBalanced
+    int parts;                   // kModeFixed: partitions per row
+    int unit;                    // tokens per unit (split modes), else 0
+    long long max_pieces;        // partial results the workspace holds
     float scale;
-    float *workspace;            // part_out followed by part_lse; nullptr when unsplit
+    float *workspace;            // part_out, part_lse, unit prefix sums; nullptr in rows mode
     size_t workspace_bytes;
     int resident_wgs;            // persistent grid: two work-groups per compute unit
     char err[256];
@@ -996,49 +1073,59 @@ thread_local char g_create_err[256] = "";
 int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 struct Plan {
-    int num_splits;
-    int split_tokens;
+    int mode;
+    int parts;
+    int unit;
 };
 
-// Most work items any call may produce: every resident work-group keeps a table of at most
-// kTableSlots items, and the grid has at least kMinGrid work-groups.
-constexpr long long kMinGrid = 256;
-constexpr long long kMaxItems = kTableSlots * kMinGrid;
+// Upper bound on the persistent grid (two work-groups per compute unit, capped), so that the
+// workspace size does not depend on the device.
+constexpr int kMaxGrid = 1024;
 
-// Partitioning.  Explicit num_splits is honoured exactly.  Otherwise: batches that already hold
-// one item per resident work-group with contexts of at most 4096 tokens stay unsplit (no
-// partial results at all); everything else gets a BASE partition of 512 KiB of K+V per kv head
-// (1024 bf16 tokens, 2048 fp8 tokens; more if the item budget requires), which the kernel
-// itself doubles up to four times per call depending on how much work seq_lens holds.
-// (Measured: items of 512 tokens lose 10-20 % to per-item costs on small batches; items of
-// 1024 tokens cost a 64-head layer 11 % against 4096-token items once the batch is large.)
+// Partitioning.  num_splits == 1 never cuts a row; num_splits == N > 1 cuts every row into
+// partitions of ceil(max_seq_len / N) tokens (rounded up to a multiple of 256).  Otherwise
+// (0): batches that already hold one row per resident work-group with contexts of at most
+// 4096 tokens are not cut (no partial results, no merge launch: measured 3 % on 160 us calls),
+// nor are batches beyond what the prefix sum in LDS holds; everything else runs balanced --
+// every work-group streams the same share of the call's tokens.
 Plan make_plan(const lamina_attn_config &c)
 {
     Plan pl;
+    pl.parts = 1;
+    pl.unit = 0;
     const long long pairs = (long long)c.max_batch * c.num_kv_heads;
-    int P;
-    if (c.num_splits >= 1) {
-        P = c.num_splits;
-    } else if (c.max_seq_len <= 4096 && pairs >= 256) {
-        P = 1;
+    if (c.num_splits == 1 || (c.num_splits == 0 && (c.max_batch > kMaxSplitBatch ||
+                                                    (c.max_seq_len <= 4096 && pairs >= 256)))) {
+        pl.mode = kModeRows;
+    } else if (c.num_splits > 1) {
+        pl.mode = kModeFixed;
+        pl.parts = c.num_splits;
+        pl.unit = round_up((c.max_seq_len + c.num_splits - 1) / c.num_splits, kChunkAlign);
     } else {
-        int target = c.kv_dtype == LAMINA_FP8_E4M3 ? 2048 : 1024;
-        while (pairs * ((c.max_seq_len + target - 1) / target) > kMaxItems)
-            target *= 2;
-        P = (c.max_seq_len + target - 1) / target;
+        pl.mode = kModeBalanced;
+        pl.unit = c.kv_dtype == LAMINA_FP8_E4M3 ? 256 : 128;   // four wavefronts x one tile
     }
-    if (P < 1)
-        P = 1;
-    int chunk = round_up((c.max_seq_len + P - 1) / P, kChunkAlign);
-    if (chunk < kChunkAlign)
-        chunk = kChunkAlign;
-    if (c.num_splits < 1)
-        P = (c.max_seq_len + chunk - 1) / chunk;          // drop partitions the rounding emptied
-    if (P < 1)
-        P = 1;
-    pl.num_splits = P;
-    pl.split_tokens = chunk;
     return pl;
+}
+
+// Units per row at most, and partial results the workspace must hold.
+long long max_units_per_row(const lamina_attn_config &c, const Plan &pl)
+{
+    if (pl.mode == kModeRows)
+        return 1;
+    if (pl.mode == kModeFixed)
+        return pl.parts;
+    return ((long long)c.max_seq_len + pl.unit - 1) / pl.unit;
+}
+
+long long max_pieces_for(const lamina_attn_config &c, const Plan &pl)
+{
+    const long long rows = (long long)c.max_batch * c.num_kv_heads;
+    if (pl.mode == kModeRows)
+        return 0;
+    if (pl.mode == kModeFixed)
+        return rows * pl.parts;                           // piece index = unit number
+    return rows + kMaxGrid;                               // piece index = row + work-group
 }
 
 const char *check_config(const lamina_attn_config *c, int *code)
@@ -1070,11 +1157,12 @@ const char *check_config(const lamina_attn_config *c, int *code)
         return "group size num_q_heads/num_kv_heads must be 1, 2, 4, 8 or 16";
     if (c->kernel != LAMINA_KERNEL_MFMA)
         return "unknown kernel family";
-    if (c->num_splits > 1) {
-        if (c->max_batch > kMaxSplitBatch)
-            return "a partitioned handle supports max_batch up to 1024";
-        if ((long long)c->max_batch * c->num_kv_heads * c->num_splits > kMaxItems)
-            return "max_batch * num_kv_heads * num_splits above 65536";
+    if (c->num_splits > 1 && c->max_batch > kMaxSplitBatch)
+        return "a partitioned handle supports max_batch up to 1024";
+    {
+        const Plan pl = make_plan(*c);
+        if ((long long)c->max_batch * c->num_kv_heads * max_units_per_row(*c, pl) > (1LL << 30))
+            return "max_batch * num_kv_heads * partitions per row above 2^30";
     }
     *code = LAMINA_OK;
     return nullptr;
@@ -1082,10 +1170,12 @@ const char *check_config(const lamina_attn_config *c, int *code)
 
 size_t workspace_bytes_for(const lamina_attn_config &c, const Plan &pl)
 {
-    if (pl.num_splits <= 1)
+    if (pl.mode == kModeRows)
         return 0;
-    // partial outputs, partial lse, and one int: the partition size the last call settled on
-    return (size_t)c.max_batch * c.num_q_heads * pl.num_splits * (kHeadDim + 1) * sizeof(float) + 16;
+    // partial outputs and lse per (piece, head of the group), then the unit prefix sums
+    const size_t G = (size_t)(c.num_q_heads / c.num_kv_heads);
+    return (size_t)max_pieces_for(c, pl) * G * (kHeadDim + 1) * sizeof(float) +
+           (size_t)round_up((c.max_batch + 1) * (int)sizeof(int), 16);
 }
 
 int fail(lamina_attn *h, int code, const char *msg)
@@ -1122,6 +1212,17 @@ class DeviceGuard {
     int prev_;
     bool ok_;
 };
+
+// Work-groups of the main pass for a call with `batch` requests: never more than can be
+// resident, never more than there can be units.
+int grid_for(const lamina_attn *h, int batch)
+{
+    const Plan pl = {h->mode, h->parts, h->unit};
+    long long wgs = (long long)batch * h->cfg.num_kv_heads * max_units_per_row(h->cfg, pl);
+    if (wgs > h->resident_wgs)
+        wgs = h->resident_wgs;
+    return (int)wgs;
+}
 
 }  // namespace
 
@@ -1162,8 +1263,10 @@ int lamina_attn_create(const lamina_attn_config *cfg, lamina_attn_t *out_handle)
     h->cfg = *cfg;
     h->group = cfg->num_q_heads / cfg->num_kv_heads;
     const Plan pl = make_plan(*cfg);
-    h->num_splits = pl.num_splits;
-    h->split_tokens = pl.split_tokens;
+    h->mode = pl.mode;
+    h->parts = pl.parts;
+    h->unit = pl.unit;
+    h->max_pieces = max_pieces_for(*cfg, pl);
     h->scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
     h->workspace = nullptr;
     h->workspace_bytes = workspace_bytes_for(*cfg, pl);
@@ -1177,14 +1280,7 @@ int lamina_attn_create(const lamina_attn_config *cfg, lamina_attn_t *out_handle)
             delete h;
             return LAMINA_ERR_HIP;
         }
-        h->resident_wgs = 2 * cus;
-        if (pl.num_splits > 1 && (h->resident_wgs < kMinGrid || cfg->max_batch > kMaxSplitBatch)) {
-            snprintf(g_create_err, sizeof g_create_err,
-                     "partitioned handles need max_batch <= %d and a device with >= %lld compute units",
-                     kMaxSplitBatch, kMinGrid / 2);
-            delete h;
-            return LAMINA_ERR_UNSUPPORTED;
-        }
+        h->resident_wgs = 2 * cus < kMaxGrid ? 2 * cus : kMaxGrid;
     }
     if (h->workspace_bytes) {
         DeviceGuard guard(cfg->device);
@@ -1195,16 +1291,6 @@ int lamina_attn_create(const lamina_attn_config *cfg, lamina_attn_t *out_handle)
             (void)hipGetLastError();
             delete h;
             return LAMINA_ERR_WORKSPACE;
-        }
-        e = hipMemset(reinterpret_cast<char *>(h->workspace) + h->workspace_bytes - 16, 0, 16);
-        if (e == hipSuccess)
-            e = hipDeviceSynchronize();
-        if (e != hipSuccess) {
-            snprintf(g_create_err, sizeof g_create_err, "clearing the workspace: %s",
-                     hipGetErrorString(e));
-            (void)hipFree(h->workspace);
-            delete h;
-            return LAMINA_ERR_HIP;
         }
     }
     *out_handle = h;
@@ -1227,22 +1313,47 @@ int lamina_attn_destroy(lamina_attn_t h)
 
 const char *lamina_attn_last_error(lamina_attn_t h) { return h ? h->err : g_create_err; }
 
-int lamina_attn_num_splits(lamina_attn_t h) { return h ? h->num_splits : 0; }
-
-int lamina_attn_split_tokens(lamina_attn_t h) { return h ? h->split_tokens : 0; }
-
-int lamina_attn_used_split_tokens(lamina_attn_t h)
+int lamina_attn_num_splits(lamina_attn_t h)
 {
     if (!h)
         return 0;
-    if (h->num_splits <= 1)
-        return h->split_tokens;
-    int used = 0;
-    DeviceGuard guard(h->cfg.device);
-    const char *at = reinterpret_cast<const char *>(h->workspace) + h->workspace_bytes - 16;
-    if (!guard.ok() || hipMemcpy(&used, at, sizeof used, hipMemcpyDeviceToHost) != hipSuccess)
-        return LAMINA_ERR_HIP;
-    return used;
+    return h->mode == kModeRows ? 1 : (h->mode == kModeFixed ? h->parts : 0);
+}
+
+int lamina_attn_split_tokens(lamina_attn_t h) { return h ? h->unit : 0; }
+
+int64_t lamina_attn_count_partials(lamina_attn_t h, const int32_t *host_seq_lens, int32_t batch)
+{
+    if (!h || !host_seq_lens || batch < 0 || batch > h->cfg.max_batch)
+        return LAMINA_ERR_INVALID_ARG;
+    if (h->mode == kModeRows)
+        return 0;
+    const int Hkv = h->cfg.num_kv_heads;
+    auto units_of = [&](int len) {
+        long long n = ((long long)len + h->unit - 1) / h->unit;
+        if (n < 1)
+            n = 1;
+        return (h->mode == kModeFixed && n > h->parts) ? (long long)h->parts : n;
+    };
+    long long total = 0;
+    for (int r = 0; r < batch; ++r)
+        total += units_of(host_seq_lens[r]);
+    const long long U = total * Hkv;
+    const int nwg = grid_for(h, batch);
+    long long pieces = 0, before = 0;
+    for (int r = 0; r < batch; ++r) {
+        const long long n = units_of(host_seq_lens[r]);
+        for (int g = 0; g < Hkv; ++g) {
+            const long long S = Hkv * before + g * n;
+            const long long np = h->mode == kModeFixed
+                                     ? n
+                                     : share_owner(U, nwg, S + n - 1) - share_owner(U, nwg, S) + 1;
+            if (np > 1)
+                pieces += np;
+        }
+        before += n;
+    }
+    return pieces * h->group;
 }
 
 int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
@@ -1307,30 +1418,25 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
     mp.Hq = c.num_q_heads;
     mp.Hkv = c.num_kv_heads;
     mp.G = h->group;
-    mp.P = h->num_splits;
-    mp.chunk = h->split_tokens;
+    mp.mode = h->mode;
+    mp.P = h->parts;
+    mp.unit = h->unit > 0 ? h->unit : 1;
     mp.batch = p->batch;
     mp.out_is_bf16 = c.out_dtype == LAMINA_BF16;
     mp.scale_log2 = h->scale * kLog2e;
-    if (h->num_splits > 1) {
+    if (h->mode != kModeRows) {
         mp.part_out = h->workspace;
-        mp.part_lse = h->workspace + (size_t)c.max_batch * c.num_q_heads * h->num_splits * kHeadDim;
-        mp.chunk_used = reinterpret_cast<int *>(
-            mp.part_lse + (size_t)c.max_batch * c.num_q_heads * h->num_splits);
-        mp.adapt = c.num_splits == 0;                     // an explicit partition count is kept
+        mp.part_lse = h->workspace + (size_t)h->max_pieces * h->group * kHeadDim;
+        mp.cum = reinterpret_cast<int *>(mp.part_lse + (size_t)h->max_pieces * h->group);
     }
 
     DeviceGuard guard(c.device);
     if (!guard.ok())
         return fail(h, LAMINA_ERR_HIP, "cannot select the handle's device");
     hipStream_t stream = static_cast<hipStream_t>(p->stream);
-    // Persistent grid: never more work-groups than can be resident, never more than items.
-    long long wgs = (long long)p->batch * c.num_kv_heads * h->num_splits;
-    if (wgs > h->resident_wgs)
-        wgs = h->resident_wgs;
-    if (h->num_splits == 1 &&
-        ((long long)p->batch * c.num_kv_heads + wgs - 1) / wgs > 0x3fffffffLL / kThreads)
+    if ((long long)p->batch * c.num_kv_heads > (1LL << 30))
         return fail(h, LAMINA_ERR_UNSUPPORTED, "batch too large");
+    const int wgs = grid_for(h, p->batch);
     const dim3 grid((unsigned)wgs), block(kThreads);
     // Kernel variant: cache dtype x layout x number of four-head Q row groups.
     const int gq = h->group <= 4 ? 1 : (h->group <= 8 ? 2 : 4);
@@ -1355,16 +1461,19 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail_hip(h, "main kernel launch", e);
-    if (h->num_splits > 1) {
+    if (h->mode != kModeRows) {
         MergeParams gp;
         gp.part_out = mp.part_out;
         gp.part_lse = mp.part_lse;
-        gp.seq_lens = seq_lens;
+        gp.cum = mp.cum;
         gp.out = out;
         gp.lse = lse;
         gp.Hq = c.num_q_heads;
-        gp.P = h->num_splits;
-        gp.chunk_used = mp.chunk_used;
+        gp.Hkv = c.num_kv_heads;
+        gp.G = h->group;
+        gp.mode = h->mode;
+        gp.nwg = wgs;
+        gp.R = p->batch;
         gp.out_is_bf16 = mp.out_is_bf16;
         gp.rows = p->batch * c.num_q_heads;
         hipLaunchKernelGGL(merge_partials_kernel,

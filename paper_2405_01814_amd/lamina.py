@@ -27,7 +27,7 @@ LAMINA_KERNEL_MFMA = 0
 
 EXPORTS = ("lamina_attn_create", "lamina_decode_attention", "lamina_attn_destroy",
            "lamina_attn_last_error", "lamina_attn_workspace_bytes", "lamina_attn_num_splits",
-           "lamina_attn_split_tokens", "lamina_attn_used_split_tokens", "lamina_append_kv",
+           "lamina_attn_split_tokens", "lamina_attn_count_partials", "lamina_append_kv",
            "lamina_fold_new_token")
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -92,8 +92,8 @@ def load():
     lib.lamina_attn_num_splits.argtypes = [vp]
     lib.lamina_attn_split_tokens.restype = ctypes.c_int
     lib.lamina_attn_split_tokens.argtypes = [vp]
-    lib.lamina_attn_used_split_tokens.restype = ctypes.c_int
-    lib.lamina_attn_used_split_tokens.argtypes = [vp]
+    lib.lamina_attn_count_partials.restype = ctypes.c_int64
+    lib.lamina_attn_count_partials.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32]
     lib.lamina_append_kv.restype = ctypes.c_int
     lib.lamina_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(lamina_call_params)]
     lib.lamina_fold_new_token.restype = ctypes.c_int
@@ -172,9 +172,15 @@ class DecodeAttention:
         self.num_splits = int(load().lamina_attn_num_splits(self.handle))
         self.split_tokens = int(load().lamina_attn_split_tokens(self.handle))
 
-    def used_split_tokens(self) -> int:
-        """Tokens per partition of the most recent call (synchronises the device)."""
-        return int(load().lamina_attn_used_split_tokens(self.handle))
+    def count_partials(self, seq_lens) -> int:
+        """Per-head partial results a call with these (host) lengths writes and merges."""
+        import numpy as np
+        lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+        n = int(load().lamina_attn_count_partials(
+            self.handle, lens.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), int(lens.size)))
+        if n < 0:
+            raise LaminaError(n, "lamina_attn_count_partials")
+        return n
 
     def close(self):
         if getattr(self, "handle", None) is not None:

@@ -188,15 +188,16 @@ def generate(w: Workload, lens: np.ndarray | None = None, threads: int = 8,
 
 
 def algorithmic_bytes(w: Workload, lens, out_bytes: int = 4, split_tokens: int = 0,
-                      with_lse: bool = True) -> dict:
+                      with_lse: bool = True, partial_results: int | None = None) -> dict:
     """Bytes one call must move if every needed byte is touched exactly once.
 
     KV: every attended (token, kv head) is one K row and one V row of D elements, read
     once and shared by the G query heads of its group -- per token and layer that is
     the 2*e*(d/G) of the paper's capacity example (Sec. 2.2.2) for one layer.  The rest
     is the per-call operator I/O of Sec. 3.1 (q in, output out) plus the small index
-    arrays, and for split-KV (split_tokens > 0: tokens per partition) the partial results
-    of every request that has more than one partition, written once and read once.
+    arrays, and for split-KV the partial results (one per query head and piece, D + 1
+    fp32 each) of every row that is cut, written once and read once: either counted from
+    fixed partitions of split_tokens tokens, or given directly as partial_results.
     """
     lens = np.asarray(lens, dtype=np.int64)
     R, Hq, Hkv, D = len(lens), w.num_q_heads, w.num_kv_heads, w.head_dim
@@ -210,7 +211,9 @@ def algorithmic_bytes(w: Workload, lens, out_bytes: int = 4, split_tokens: int =
         idx += int(((lens + w.block_size - 1) // w.block_size).sum()) * 4
     scales = 2 * R * Hkv * 4 if w.kv_dtype == "fp8" else 0
     partials = 0
-    if split_tokens > 0:
+    if partial_results is not None:
+        partials = 2 * int(partial_results) * (D + 1) * 4
+    elif split_tokens > 0:
         parts = (lens + split_tokens - 1) // split_tokens
         partials = 2 * int(parts[parts > 1].sum()) * Hq * (D + 1) * 4
     total = kv + q + o + lse + idx + scales + partials

@@ -421,35 +421,64 @@ def test_append_then_two_phase_equals_one_phase(name):
     op.close()
 
 
-def test_partition_size_adapts_to_the_batch_and_is_reported():
+def brute_force_partials(lens, Hkv, G, unit, nwg, parts=None):
+    """Deal the unit stream to work-groups one unit at a time and count the pieces of cut rows."""
+    units = [max(1, -(-int(n) // unit)) for n in lens]
+    if parts is not None:
+        units = [min(parts, u) for u in units]
+    owner_of_unit = []
+    U = sum(units) * Hkv
+    q, rem = divmod(U, nwg)
+    for j in range(nwg):
+        owner_of_unit += [j] * (q + (1 if j < rem else 0))
+    assert len(owner_of_unit) == U
+    total, at = 0, 0
+    for n in units:
+        for _ in range(Hkv):
+            pieces = n if parts is not None else len(set(owner_of_unit[at:at + n]))
+            at += n
+            if pieces > 1:
+                total += pieces
+    return total * G
+
+
+def test_balanced_shares_follow_the_batch_and_partials_are_counted():
     d = dev()
     w = W.WORKLOADS["llama3_8b_ctx4096"]
-    # small batch, long contexts: the base size (1024 tokens) stays
-    b = sized("llama3_8b_ctx4096", [8192, 6000])
-    op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=64, max_seq_len=8192)
-    assert (op.num_splits, op.split_tokens) == (8, 1024)
-    assert op.used_split_tokens() == 0                    # nothing has run yet
+    nwg = min(1024, 2 * torch.cuda.get_device_properties(0).multi_processor_count)
+    op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=64, max_seq_len=65536)
+    assert (op.num_splits, op.split_tokens) == (0, 128)
+    # a skewed batch: one long row is spread over many work-groups, short and empty ones are not cut
+    lens = [50000, 3, 0, 700, 129, 4096]
+    b = sized("llama3_8b_ctx4096", lens)
     t = {k: v.to(d) for k, v in b.items() if isinstance(v, torch.Tensor)}
     out, lse = op(t["q"], t["k"], t["v"], t["seq_lens"])
     torch.cuda.synchronize()
-    assert op.used_split_tokens() == 1024
     check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b), "bf16_f32")
-    # a big uniform batch on the same handle: partitions are coarsened, results still right
-    b = sized("llama3_8b_ctx4096", [8192] * 64)
+    n = op.count_partials(lens)
+    assert n == brute_force_partials(lens, w.num_kv_heads, 4, 128, nwg) and n > 0
+    # a big uniform batch on the same handle: one row per work-group, nothing is cut
+    lens = [8192] * 64
+    b = sized("llama3_8b_ctx4096", lens)
     t = {k: v.to(d) for k, v in b.items() if isinstance(v, torch.Tensor)}
     out, lse = op(t["q"], t["k"], t["v"], t["seq_lens"])
     torch.cuda.synchronize()
-    assert op.used_split_tokens() == 2048
     pairs = sample_pairs(b, 40, 9)
     check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b, pairs=pairs),
           "bf16_f32", pairs=pairs)
+    assert op.count_partials(lens) == brute_force_partials(lens, w.num_kv_heads, 4, 128, nwg)
+    if nwg == 512:
+        assert op.count_partials(lens) == 0
     op.close()
-    # an explicit partition count is never changed
+    # an explicit partition count is kept exactly
     op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=64, max_seq_len=8192,
                                 num_splits=16)
     out, lse = op(t["q"], t["k"], t["v"], t["seq_lens"])
     torch.cuda.synchronize()
-    assert (op.num_splits, op.split_tokens, op.used_split_tokens()) == (16, 512, 512)
+    assert (op.num_splits, op.split_tokens) == (16, 512)
+    assert op.count_partials(lens) == 64 * w.num_q_heads * 16
+    assert op.count_partials([8192, 100, 513]) == brute_force_partials(
+        [8192, 100, 513], w.num_kv_heads, 4, 512, nwg, parts=16) == (16 + 2) * w.num_q_heads
     check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b, pairs=pairs),
           "bf16_f32", pairs=pairs)
     op.close()
@@ -457,17 +486,20 @@ def test_partition_size_adapts_to_the_batch_and_is_reported():
 
 def test_partitioned_handle_limits_are_reported_at_creation():
     dev()
-    # unsplit handles take any batch; partitioned ones are limited by the LDS tables
+    # handles that never cut rows take any batch; so does the library's own choice, by not cutting
     op = lamina.DecodeAttention(8, 8, max_batch=5000, max_seq_len=2048)
+    assert op.num_splits == 1 and op.count_partials([2048] * 5000) == 0
+    op.close()
+    op = lamina.DecodeAttention(8, 1, max_batch=2000, max_seq_len=100000)
     assert op.num_splits == 1
     op.close()
+    # explicit partitions need the batch to fit the prefix sum the kernel keeps in LDS
     with pytest.raises(lamina.LaminaError) as ei:
-        lamina.DecodeAttention(8, 1, max_batch=2000, max_seq_len=100000)
+        lamina.DecodeAttention(8, 1, max_batch=2000, max_seq_len=100000, num_splits=4)
     assert ei.value.code == lamina.LAMINA_ERR_UNSUPPORTED
     with pytest.raises(lamina.LaminaError) as ei:
-        lamina.DecodeAttention(8, 8, max_batch=1024, max_seq_len=8192, num_splits=16)
+        lamina.DecodeAttention(64, 64, max_batch=1024, max_seq_len=4_000_000)
     assert ei.value.code == lamina.LAMINA_ERR_UNSUPPORTED
-    # the library's own choice coarsens the base partition until the item budget holds
     op = lamina.DecodeAttention(8, 8, max_batch=1024, max_seq_len=32768)
-    assert op.num_splits * 1024 * 8 <= 65536 and op.num_splits * op.split_tokens >= 32768
+    assert (op.num_splits, op.split_tokens) == (0, 128)
     op.close()

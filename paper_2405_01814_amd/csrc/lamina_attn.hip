@@ -35,6 +35,8 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 // Read-only index arrays are read through the constant address space so that uniform reads
 // stay on the scalar unit (and off the in-order vector-memory counter) inside the tile loop.
 typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
@@ -124,22 +126,25 @@ __device__ __forceinline__ unsigned short bf16_bits(float x)
     return __builtin_bit_cast(unsigned short, static_cast<__bf16>(x));
 }
 
-// Four e4m3fn bytes -> four bf16 values (exact: every e4m3fn value is a bf16 value).
-__device__ __forceinline__ bf16x4 fp8x4_to_bf16(unsigned word)
-{
-    const bf16x2 lo = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, 1.0f, false);   // bytes 0, 1
-    const bf16x2 hi = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, 1.0f, true);    // bytes 2, 3
-    bf16x4 r;
-    r[0] = lo[0];
-    r[1] = lo[1];
-    r[2] = hi[0];
-    r[3] = hi[1];
-    return r;
-}
-
 __device__ __forceinline__ bf16x8 join_bf16x4(bf16x4 a, bf16x4 b)
 {
     return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// x = hi + lo with hi and lo both e4m3fn (round to nearest even): four values -> one dword of
+// hi bytes and one of lo bytes, value i in byte i.  |x| must stay below 448 (the convert does
+// not saturate).  hi keeps 4 significant bits and lo the next 4, so a value with at most 8
+// significant bits (any bf16) splits exactly unless lo falls below 2^-9.
+__device__ __forceinline__ void split_fp8x4(float x0, float x1, float x2, float x3, int &hi, int &lo)
+{
+    int h = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, 0, false);
+    h = __builtin_amdgcn_cvt_pk_fp8_f32(x2, x3, h, true);
+    const f32x2 b01 = __builtin_amdgcn_cvt_pk_f32_fp8(h, false);
+    const f32x2 b23 = __builtin_amdgcn_cvt_pk_f32_fp8(h, true);
+    int l = __builtin_amdgcn_cvt_pk_fp8_f32(x0 - b01[0], x1 - b01[1], 0, false);
+    l = __builtin_amdgcn_cvt_pk_fp8_f32(x2 - b23[0], x3 - b23[1], l, true);
+    hi = h;
+    lo = l;
 }
 
 // Work-group barrier that orders LDS traffic only.  Unlike __syncthreads() it does not wait
@@ -218,7 +223,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     constexpr int LPR = ROWB / 16;                        // lanes that cover one V row
     constexpr int RPI = 64 / LPR;                         // V rows per load instruction
     constexpr int VBUF = TILE * VSTRIDE;                  // V staging bytes per wavefront
-    constexpr bool SPLIT_P = !FP8;                        // carry p as hi + lo bf16 halves
+    // fp8 caches: probabilities are carried as 2^kPShift * p so that their fp8 halves stay
+    // normal numbers down to p = 2^-13; numerator and denominator share the factor.
+    constexpr float kPShift = FP8 ? 7.0f : 0.0f;
     // Keep the next item's Q rows in registers for a whole item?  Only where the register
     // file has room (not with the fp8 tile, not with 16 head rows); otherwise the rows are
     // fetched when the item starts, which costs that wavefront one exposed cache latency.
@@ -468,7 +475,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     // rows -- one 1 KiB load instruction per four heads, lane = (head, 16-byte piece) -- and
     // turned into the operand layout through this wavefront's (idle between items) staging
     // area, because vector-memory instructions, not bytes, are what an item boundary costs.
+    //
+    // bf16 caches: four k-steps of 8 bf16 dims.  fp8 caches: the matrix cores multiply fp8 by
+    // fp8, so Q is split per head into q * 2^a = hi + lo with both halves e4m3fn (exact, see
+    // split_fp8x4; a puts the row's largest magnitude into [128, 256)), K needs no conversion
+    // at all, and one 16x16x128 MFMA per half covers the whole head dimension: the lane holds
+    // dims quad*32 .. quad*32+31 of its row, for Q and for K alike.
     bf16x8 qop[4];
+    i32x8 q8hi, q8lo;
+    float q_unscale = 1.0f;         // 2^-a of the head in this lane's column (fp8 caches)
     auto request_q = [&](int r, int g, u32x4(&raw)[GQ]) {
         const unsigned char *qg = static_cast<const unsigned char *>(prm.q) +
                                   ((size_t)r * prm.Hq + g * G) * (kHeadDim * 2);
@@ -485,14 +500,45 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
 #pragma unroll
         for (int i = 0; i < GQ; ++i)
             *reinterpret_cast<u32x4 *>(vbuf + (i * 4 + (lane >> 4)) * 256 + (lane & 15) * 16) = raw[i];
+        if (FP8) {
+            float f[32];
+            float amax = 0.0f;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            // The dims a lane holds in step s must be the dims its K register holds there.
-            const int chunk8 = FP8 ? (((s >> 1) * 4 + quad) * 2 + (s & 1)) : (s * 4 + quad);
-            bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-            qop[s] = z;
-            if (col < GQ * 4)                             // rows at or above G hold zeros
-                qop[s] = *reinterpret_cast<const bf16x8 *>(vbuf + col * 256 + chunk8 * 16);
+            for (int i = 0; i < 4; ++i) {
+                u32x4 t = {0u, 0u, 0u, 0u};
+                if (col < GQ * 4)                         // rows at or above G hold zeros
+                    t = *reinterpret_cast<const u32x4 *>(vbuf + col * 256 + quad * 64 + i * 16);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    f[i * 8 + d * 2] = __builtin_bit_cast(float, t[d] << 16);
+                    f[i * 8 + d * 2 + 1] = __builtin_bit_cast(float, t[d] & 0xffff0000u);
+                    amax = fmaxf(amax, fmaxf(fabsf(f[i * 8 + d * 2]), fabsf(f[i * 8 + d * 2 + 1])));
+                }
+            }
+            amax = fmaxf(amax, __shfl_xor(amax, 16));
+            amax = fmaxf(amax, __shfl_xor(amax, 32));
+            const int e = (int)((__builtin_bit_cast(unsigned, amax) >> 23) & 255u);
+            int a = (amax > 0.0f) ? 134 - e : 0;          // amax * 2^a in [128, 256)
+            a = max(-100, min(100, a));
+            const float up = __builtin_bit_cast(float, (unsigned)(127 + a) << 23);
+            q_unscale = __builtin_bit_cast(float, (unsigned)(127 - a) << 23);
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+                int h, l;
+                split_fp8x4(f[d * 4] * up, f[d * 4 + 1] * up, f[d * 4 + 2] * up, f[d * 4 + 3] * up, h, l);
+                q8hi[d] = h;
+                q8lo[d] = l;
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                // The dims a lane holds in step s must be the dims its K operand holds there.
+                const int chunk8 = s * 4 + quad;
+                bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+                qop[s] = z;
+                if (col < GQ * 4)                         // rows at or above G hold zeros
+                    qop[s] = *reinterpret_cast<const bf16x8 *>(vbuf + col * 256 + chunk8 * 16);
+            }
         }
     };
     auto score_scale = [&](int r, int g) {
@@ -515,8 +561,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
 
     // First half of a tile: everything that reads the tile's load registers.
     auto consume = [&](const u32x4(&kr)[KR], const u32x4(&vr)[VR], f32x4(&sc)[NSUB]) {
-        // K rows -> LDS (pitch KSTRIDE) -> MFMA A-operand layout (row = token col, the lane
-        // holds the 16-byte piece s*4 + quad of that row in k-step s).  The staging area is
+        // K rows -> LDS (pitch KSTRIDE) -> MFMA A-operand layout (row = token col; bf16: the
+        // lane holds the 16-byte piece s*4 + quad of that row in k-step s; fp8: its 32-byte
+        // piece quad, untouched -- the matrix cores take e4m3 as it is).  The staging area is
         // used for K first and for V afterwards; LDS operations of a wavefront execute in
         // order, so V cannot overtake the K reads.
 #pragma unroll
@@ -527,17 +574,21 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            const unsigned char *krow = vbuf + (sub * 16 + col) * KSTRIDE + quad * 16;
             if (FP8) {
+                const unsigned char *krow = vbuf + (sub * 16 + col) * KSTRIDE + quad * 32;
+                const u32x4 k0 = *reinterpret_cast<const u32x4 *>(krow);
+                const u32x4 k1 = *reinterpret_cast<const u32x4 *>(krow + 16);
+                i32x8 kop;
 #pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2) {
-                    const u32x4 raw = *reinterpret_cast<const u32x4 *>(krow + s2 * 64);
-                    const bf16x8 lo = join_bf16x4(fp8x4_to_bf16(raw[0]), fp8x4_to_bf16(raw[1]));
-                    const bf16x8 hi = join_bf16x4(fp8x4_to_bf16(raw[2]), fp8x4_to_bf16(raw[3]));
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, qop[2 * s2], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi, qop[2 * s2 + 1], acc, 0, 0, 0);
+                for (int d = 0; d < 4; ++d) {
+                    kop[d] = (int)k0[d];
+                    kop[4 + d] = (int)k1[d];
                 }
+                // e4m3 x e4m3, no block scales (scale operands 0)
+                acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kop, q8hi, acc, 0, 0, 0, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(kop, q8lo, acc, 0, 0, 0, 0, 0, 0);
             } else {
+                const unsigned char *krow = vbuf + (sub * 16 + col) * KSTRIDE + quad * 16;
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
                     const bf16x8 kop = *reinterpret_cast<const bf16x8 *>(krow + s * 64);
@@ -574,16 +625,32 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         const float alpha = fast_exp2(m_run - m_new);     // exp2(-inf) = 0 on the first tile
         m_run = m_new;
         float psum = 0.0f;
-        bf16x8 p_hi[NPAIR], p_lo[NPAIR];
+        bf16x8 p_hi[NPAIR], p_lo[NPAIR];                  // bf16 caches: p = hi + lo, both bf16
+        long p8_hi[NPAIR], p8_lo[NPAIR];                  // fp8 caches: 2^7 p = hi + lo, both e4m3
+        float pj[NSUB * 4];
 #pragma unroll
         for (int jj = 0; jj < NSUB * 4; ++jj) {
-            const float pj = fast_exp2(x[jj] - m_new);
-            psum += pj;
-            // p = hi + lo with both halves bf16: keeps ~16 significant bits through the MFMA
-            const __bf16 h = static_cast<__bf16>(pj);
-            p_hi[jj >> 3][jj & 7] = h;
-            if (SPLIT_P)
-                p_lo[jj >> 3][jj & 7] = static_cast<__bf16>(pj - static_cast<float>(h));
+            pj[jj] = fast_exp2(x[jj] - (m_new - kPShift));
+            psum += pj[jj];
+        }
+        if (FP8) {
+#pragma unroll
+            for (int pp = 0; pp < NPAIR; ++pp) {
+                int h0, l0, h1, l1;
+                split_fp8x4(pj[pp * 8], pj[pp * 8 + 1], pj[pp * 8 + 2], pj[pp * 8 + 3], h0, l0);
+                split_fp8x4(pj[pp * 8 + 4], pj[pp * 8 + 5], pj[pp * 8 + 6], pj[pp * 8 + 7], h1, l1);
+                i32x2 h = {h0, h1}, l = {l0, l1};
+                p8_hi[pp] = __builtin_bit_cast(long, h);
+                p8_lo[pp] = __builtin_bit_cast(long, l);
+            }
+        } else {
+#pragma unroll
+            for (int jj = 0; jj < NSUB * 4; ++jj) {
+                // p = hi + lo with both halves bf16: keeps ~16 significant bits through the MFMA
+                const __bf16 h = static_cast<__bf16>(pj[jj]);
+                p_hi[jj >> 3][jj & 7] = h;
+                p_lo[jj >> 3][jj & 7] = static_cast<__bf16>(pj[jj] - static_cast<float>(h));
+            }
         }
         l_run = l_run * alpha + psum;
         if (__any(alpha != 1.0f)) {
@@ -595,17 +662,20 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         for (int db = 0; db < 8; ++db) {
 #pragma unroll
             for (int pp = 0; pp < NPAIR; ++pp) {
-                bf16x8 vop;
                 if (FP8) {
-                    // 8 rows x 16 byte-columns per 16-lane block; lane supplies row col/2
+                    // 8 rows x 16 byte-columns per 16-lane block; lane supplies row col/2.
+                    // The transposed bytes are the MFMA operand as they are.
                     const int rr = col >> 1;
                     const int trow =
                         pp * 32 + ((rr < 4) ? (quad * 4 + rr) : (16 + quad * 4 + rr - 4));
                     const unsigned char *a = vbuf + trow * VSTRIDE + db * 16 + (col & 1) * 8;
                     const i32x2 raw = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
                         (i32x2 __attribute__((address_space(3))) *)(a));
-                    vop = join_bf16x4(fp8x4_to_bf16((unsigned)raw[0]),
-                                      fp8x4_to_bf16((unsigned)raw[1]));
+                    const long vop = __builtin_bit_cast(long, raw);
+                    o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(vop, p8_hi[pp],
+                                                                          o_acc[db], 0, 0, 0);
+                    o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(vop, p8_lo[pp],
+                                                                          o_acc[db], 0, 0, 0);
                 } else {
                     // 4 rows x 16 columns per 16-lane block; lane supplies row col/4, 4 columns
                     const unsigned char *a = vbuf + (pp * 32 + quad * 4 + (col >> 2)) * VSTRIDE +
@@ -614,14 +684,13 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                         (s16x4 __attribute__((address_space(3))) *)(a));
                     const s16x4 rb = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                         (s16x4 __attribute__((address_space(3))) *)(a + 16 * VSTRIDE));
-                    vop = join_bf16x4(__builtin_bit_cast(bf16x4, ra),
-                                      __builtin_bit_cast(bf16x4, rb));
-                }
-                o_acc[db] =
-                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_hi[pp], o_acc[db], 0, 0, 0);
-                if (SPLIT_P)
+                    const bf16x8 vop = join_bf16x4(__builtin_bit_cast(bf16x4, ra),
+                                                   __builtin_bit_cast(bf16x4, rb));
+                    o_acc[db] =
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_hi[pp], o_acc[db], 0, 0, 0);
                     o_acc[db] =
                         __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p_lo[pp], o_acc[db], 0, 0, 0);
+                }
             }
         }
     };
@@ -688,7 +757,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             const bool empty = !(L > 0.0f);               // a request with no tokens at all
             s_wgt[quad * kMaxGroup + col] = empty ? 0.0f : e * vs * __builtin_amdgcn_rcpf(L);
             if (quad == 0 && col < G) {
-                const float lse_nat = empty ? -INFINITY : (M + __builtin_amdgcn_logf(L)) * kLn2;
+                const float lse_nat =
+                    empty ? -INFINITY : (M + __builtin_amdgcn_logf(L) - kPShift) * kLn2;
                 const size_t row = (size_t)r * prm.Hq + g * G + col;
                 if (whole) {
                     if (prm.lse)
@@ -767,6 +837,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                 wait_vmem_all();                          // also keeps the tile loop's waits exact
             }
             install_q(qn);
+            if (FP8)
+                c_log2 *= q_unscale;                      // per head: undo the 2^a of the Q split
             find_next(nxt);
             // Where refills go once this item's tiles are exhausted: the next item's first
             // two slots, or -- at the very end -- harmless reloads of this item's last row.

@@ -13,7 +13,8 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
-_SRC = os.path.join(_HERE, "csrc", "lamina_attn.hip")
+_SRCS = [os.path.join(_HERE, "csrc", "lamina_attn.hip"),
+         os.path.join(_HERE, "csrc", "lamina_seqno.hip")]
 _INC = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "liblamina_attn.so")
 
@@ -28,7 +29,11 @@ LAMINA_KERNEL_MFMA = 0
 EXPORTS = ("lamina_attn_create", "lamina_decode_attention", "lamina_attn_destroy",
            "lamina_attn_last_error", "lamina_attn_workspace_bytes", "lamina_attn_num_splits",
            "lamina_attn_split_tokens", "lamina_attn_count_partials", "lamina_append_kv",
-           "lamina_fold_new_token")
+           "lamina_fold_new_token",
+           "lamina_seqno_alloc", "lamina_seqno_free", "lamina_seqno_wait", "lamina_seqno_signal")
+
+LAMINA_SEQNO_REACHED = 0
+LAMINA_SEQNO_TIMED_OUT = 1
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -56,7 +61,7 @@ class lamina_call_params(ctypes.Structure):
 def build_library(verbose: bool = False) -> str:
     """Compile the HIP library for gfx950 in-tree with hipcc; returns its path."""
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", _INC, "-o", LIB_PATH, _SRC]
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", _INC, "-o", LIB_PATH, *_SRCS]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
@@ -96,6 +101,15 @@ def load():
     lib.lamina_attn_count_partials.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32]
     lib.lamina_append_kv.restype = ctypes.c_int
     lib.lamina_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(lamina_call_params)]
+    u64p, i32p = ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_int32)
+    lib.lamina_seqno_alloc.restype = ctypes.c_int
+    lib.lamina_seqno_alloc.argtypes = [ctypes.POINTER(u64p), ctypes.POINTER(i32p)]
+    lib.lamina_seqno_free.restype = ctypes.c_int
+    lib.lamina_seqno_free.argtypes = [u64p, i32p]
+    lib.lamina_seqno_wait.restype = ctypes.c_int
+    lib.lamina_seqno_wait.argtypes = [u64p, ctypes.c_uint64, ctypes.c_uint32, i32p, vp]
+    lib.lamina_seqno_signal.restype = ctypes.c_int
+    lib.lamina_seqno_signal.argtypes = [u64p, ctypes.c_uint64, vp]
     lib.lamina_fold_new_token.restype = ctypes.c_int
     lib.lamina_fold_new_token.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp,
                                           ctypes.POINTER(lamina_call_params)]
@@ -151,6 +165,70 @@ def lamina_attn_workspace_bytes(cfg: lamina_attn_config) -> int:
 
 
 # ---- convenience wrapper over torch tensors ---------------------------------------------
+
+def lamina_seqno_alloc():
+    """Returns (status, seqno pointer, status-word pointer); both ctypes pointers into pinned memory."""
+    sq, st = ctypes.POINTER(ctypes.c_uint64)(), ctypes.POINTER(ctypes.c_int32)()
+    rc = load().lamina_seqno_alloc(ctypes.byref(sq), ctypes.byref(st))
+    return rc, sq, st
+
+
+def lamina_seqno_free(seqno, status=None) -> int:
+    return load().lamina_seqno_free(seqno, status)
+
+
+def lamina_seqno_wait(seqno, target: int, timeout_us: int, status, stream) -> int:
+    return load().lamina_seqno_wait(seqno, target, timeout_us, status, stream)
+
+
+def lamina_seqno_signal(seqno, value: int, stream) -> int:
+    return load().lamina_seqno_signal(seqno, value, stream)
+
+
+class Seqno:
+    """A sequence number in pinned memory plus a status word for bounded waits (Sec. 4.1,
+    device-side polling).  `value` / `status` read and write the words from the host."""
+
+    def __init__(self):
+        rc, self._seqno, self._status = lamina_seqno_alloc()
+        if rc != LAMINA_OK:
+            self._seqno = None
+            raise LaminaError(rc, "lamina_seqno_alloc")
+
+    @property
+    def value(self) -> int:
+        return int(self._seqno[0])
+
+    @value.setter
+    def value(self, v: int):
+        self._seqno[0] = v                     # an aligned 64-bit store (x86: release ordering)
+
+    @property
+    def status(self) -> int:
+        return int(self._status[0])
+
+    def wait(self, target: int, timeout_us: int = 0, stream=None) -> None:
+        """Enqueue a bounded wait for value >= target on `stream` (a torch stream or None)."""
+        rc = lamina_seqno_wait(self._seqno, target, timeout_us, self._status, _stream_handle(stream))
+        if rc != LAMINA_OK:
+            raise LaminaError(rc, "lamina_seqno_wait")
+
+    def signal(self, value: int, stream=None) -> None:
+        rc = lamina_seqno_signal(self._seqno, value, _stream_handle(stream))
+        if rc != LAMINA_OK:
+            raise LaminaError(rc, "lamina_seqno_signal")
+
+    def close(self):
+        if getattr(self, "_seqno", None) is not None:
+            lamina_seqno_free(self._seqno, self._status)
+            self._seqno = None
+
+
+def _stream_handle(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
 
 _DTYPES = {"bf16": LAMINA_BF16, "fp8": LAMINA_FP8_E4M3, "f32": LAMINA_F32}
 

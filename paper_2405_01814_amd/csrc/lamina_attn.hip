@@ -1154,20 +1154,28 @@ struct Plan {
 // workspace size does not depend on the device.
 constexpr int kMaxGrid = 1024;
 
+// Contexts up to this many tokens are never cut by the library's own choice: one work-group
+// streams such a row in ~15 us, less than cutting it saves once the merge launch is paid.
+constexpr int kShortContext = 1024;
+
 // Partitioning.  num_splits == 1 never cuts a row; num_splits == N > 1 cuts every row into
 // partitions of ceil(max_seq_len / N) tokens (rounded up to a multiple of 256).  Otherwise
-// (0): batches that already hold one row per resident work-group with contexts of at most
-// 4096 tokens are not cut (no partial results, no merge launch: measured 3 % on 160 us calls),
-// nor are batches beyond what the prefix sum in LDS holds; everything else runs balanced --
-// every work-group streams the same share of the call's tokens.
+// (0) rows are not cut when that cannot pay for the partial results and the merge launch --
+// short contexts; batches that already hold a row per half (contexts up to 2048) or per whole
+// (up to 4096) of the resident work-groups (measured: 160 rows of 2048 tokens take 32 us uncut,
+// 39 us balanced; a 160 us call loses 3 % to the merge launch alone) -- nor for batches beyond
+// what the prefix sum in LDS holds; everything else runs balanced: every work-group streams
+// the same share of the call's tokens.
 Plan make_plan(const lamina_attn_config &c)
 {
     Plan pl;
     pl.parts = 1;
     pl.unit = 0;
     const long long pairs = (long long)c.max_batch * c.num_kv_heads;
-    if (c.num_splits == 1 || (c.num_splits == 0 && (c.max_batch > kMaxSplitBatch ||
-                                                    (c.max_seq_len <= 4096 && pairs >= 256)))) {
+    if (c.num_splits == 1 ||
+        (c.num_splits == 0 && (c.max_batch > kMaxSplitBatch || c.max_seq_len <= kShortContext ||
+                               (c.max_seq_len <= 2048 && pairs >= 128) ||
+                               (c.max_seq_len <= 4096 && pairs >= 256)))) {
         pl.mode = kModeRows;
     } else if (c.num_splits > 1) {
         pl.mode = kModeFixed;

@@ -484,6 +484,33 @@ def test_balanced_shares_follow_the_batch_and_partials_are_counted():
     op.close()
 
 
+def test_one_long_row_is_spread_over_every_work_group():
+    # a single (request, kv head) row of 300 000 tokens: every work-group takes a piece of it
+    # and the merge combines several hundred partial results (more than one wavefront of them)
+    w = W.WORKLOADS["llama_65b_mha_ctx4096"]
+    b = sized("llama_65b_mha_ctx4096", [300_000], num_q_heads=1, num_kv_heads=1)
+    got, info = gpu_of(b)
+    assert info == (0, 128)
+    check(got, oracle_of(b), "bf16_f32")
+    # the same row with a few short neighbours, G = 8
+    b = sized("llama3_70b_headshare_paged", [5, 200_000, 129, 1])
+    got, info = gpu_of(b)
+    assert info == (0, 128)
+    check(got, oracle_of(b), "bf16_f32")
+
+
+def test_the_largest_batch_of_a_handle_that_cuts_rows():
+    # 1024 requests (the limit of the in-kernel prefix sum), lengths 0 .. 1500: thousands of
+    # short rows, most work-groups hold several whole rows and the tails of two more
+    rng = np.random.default_rng(7)
+    lens = rng.integers(0, 1501, size=1024).astype(np.int32)
+    lens[:4] = [0, 1500, 1, 128]
+    b = sized("llama_65b_mha_ctx4096", lens, num_q_heads=4, num_kv_heads=2)
+    got, info = gpu_of(b, max_seq_len=100_000)             # a capacity that makes the handle cut rows
+    assert info == (0, 128)
+    check(got, oracle_of(b), "bf16_f32")
+
+
 def test_partitioned_handle_limits_are_reported_at_creation():
     dev()
     # handles that never cut rows take any batch; so does the library's own choice, by not cutting

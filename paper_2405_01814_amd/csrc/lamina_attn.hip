@@ -904,7 +904,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
 // dealing rule; a row that was never cut was already written to out/lse by the main pass.
 // Lane p first holds piece p's weight (the log-sum-exp reduction is two wave reductions);
 // then the two half-waves take alternate pieces, each lane four output columns, sixteen
-// independent loads in flight per step.
+// pieces' loads in flight per step.
 // -------------------------------------------------------------------------------------------
 constexpr int kMergeRowsPerBlock = 4;
 
@@ -953,15 +953,25 @@ __global__ __launch_bounds__(64 * kMergeRowsPerBlock) void merge_partials_kernel
         const float e = (p0 + lane < np) ? __expf(pl[(size_t)(p0 + lane) * pstride] - M) : 0.0f;
         W += e;
         const int cnt = min(64, np - p0);
-#pragma unroll 8
-        for (int i = 0; i < (cnt + 1) / 2; ++i) {         // same trip count in both half-waves
-            const int p = 2 * i + half;
-            const int pc = min(p, cnt - 1);
-            float wgt = __shfl(e, pc);
-            wgt = (p < cnt) ? wgt : 0.0f;
-            const f32x4 t = *reinterpret_cast<const f32x4 *>(
-                po + (size_t)(p0 + pc) * pstride * kHeadDim + c4);
-            o += wgt * t;
+        // Eight pieces per half-wave at a time, all loads issued before the first use.  (A
+        // loop with a run-time trip count is not unrolled around the cross-lane read, and the
+        // loads would go out one round trip after the other.)  Pieces beyond cnt re-read the
+        // last one with weight zero.
+        for (int i0 = 0; i0 < (cnt + 1) / 2; i0 += 8) {
+            f32x4 t[8];
+            float wgt[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int p = 2 * (i0 + k) + half;
+                const int pc = min(p, cnt - 1);
+                wgt[k] = __shfl(e, pc);
+                wgt[k] = (p < cnt) ? wgt[k] : 0.0f;
+                t[k] = *reinterpret_cast<const f32x4 *>(
+                    po + (size_t)(p0 + pc) * pstride * kHeadDim + c4);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                o += wgt[k] * t[k];
         }
     }
 #pragma unroll

@@ -6,15 +6,17 @@
 // grow with the batch (Sec. 2.2.2), so the kernel is organised around streaming K and V
 // from HBM exactly once:
 //
-//   * one work-group (4 wavefronts) per (request, kv head, KV partition); the G query heads
-//     of the group share every K/V tile that is loaded;
-//   * every wavefront streams its own 32-token tiles with non-temporal 128-bit loads, one
-//     tile ahead of the arithmetic, and never synchronises with its neighbours until the end;
+//   * a persistent grid of 4-wavefront work-groups shares out the (request, kv head) rows --
+//     whole, in fixed partitions, or in equal token shares cut from seq_lens on the device;
+//     the G query heads of a group share every K/V tile that is loaded;
+//   * every wavefront streams its own 32-token tiles (64 for fp8 caches) with non-temporal
+//     128-bit loads of whole rows, one tile ahead of the arithmetic, and never synchronises
+//     with its neighbours until an item ends;
 //   * q.K^T and p.V run on the matrix cores (16x16x32 bf16 MFMA, the G heads padded to 16
-//     columns) so that the vector ALU only does the softmax; K goes from HBM straight into
-//     the MFMA operand layout, V is staged through LDS and read back transposed;
-//   * partitions keep (A_q(I), ln S_q(I)) of Sec. 4.2.2 and a second kernel combines them
-//     with the divide-and-conquer identity of that section.
+//     columns; e4m3 operands for fp8 caches) so that the vector ALU only does the softmax; K
+//     and V tiles are staged through LDS into the operand layouts (V transposed);
+//   * pieces of a cut row keep (A_q(I), ln S_q(I)) of Sec. 4.2.2 and a second kernel combines
+//     them with the divide-and-conquer identity of that section.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -158,14 +160,6 @@ __device__ __forceinline__ void lds_barrier()
 
 // Wait until every vector-memory operation this wavefront has issued is complete.
 __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-
-__device__ __forceinline__ void store_out(void *out, int out_is_bf16, size_t idx, float x)
-{
-    if (out_is_bf16)
-        static_cast<unsigned short *>(out)[idx] = bf16_bits(x);
-    else
-        static_cast<float *>(out)[idx] = x;
-}
 
 // -------------------------------------------------------------------------------------------
 // Main pass: a persistent kernel.  The grid is a fixed number of work-groups (two per compute

@@ -255,6 +255,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         return mode == kModeFixed ? min(prm.P, n) : n;
     };
     unsigned char *vbuf = smem + w * VBUF;                // this wavefront's staging area
+    // The lane number as a value the compiler cannot see through.  Code at item boundaries
+    // derives its lane-dependent offsets from it, so that they are recomputed there instead of
+    // being carried (and, with the register file full, spilled) across the tile loop: a spill
+    // reload is a vector-memory access and would wait behind the two prefetched tiles.
+    auto fresh_lane = [&]() {
+        int l = lane;
+        asm volatile("" : "+v"(l));
+        return l;
+    };
 
     if (tid < kWaves)
         s_busy[tid] = 0;
@@ -479,6 +488,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     i32x8 q8hi, q8lo;
     float q_unscale = 1.0f;         // 2^-a of the head in this lane's column (fp8 caches)
     auto request_q = [&](int r, int g, u32x4(&raw)[GQ]) {
+        const int lane = fresh_lane();
         const unsigned char *qg = static_cast<const unsigned char *>(prm.q) +
                                   ((size_t)r * prm.Hq + g * G) * (kHeadDim * 2);
 #pragma unroll
@@ -491,6 +501,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         }
     };
     auto install_q = [&](const u32x4(&raw)[GQ]) {
+        const int lane = fresh_lane();
+        const int col = lane & 15;
+        const int quad = lane >> 4;
 #pragma unroll
         for (int i = 0; i < GQ; ++i)
             *reinterpret_cast<u32x4 *>(vbuf + (i * 4 + (lane >> 4)) * 256 + (lane & 15) * 16) = raw[i];
@@ -695,6 +708,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     // cross-partition merge) and writes the item's result.  A wavefront can be at most one
     // item ahead: it may not overwrite its parked triple before that item was combined.
     auto finalize = [&](const Piece &id) {
+        const int lane = fresh_lane();
+        const int col = lane & 15;
+        const int quad = lane >> 4;
         l_run += __shfl_xor(l_run, 16);
         l_run += __shfl_xor(l_run, 32);
         {

@@ -221,9 +221,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     // normal numbers down to p = 2^-13; numerator and denominator share the factor.
     constexpr float kPShift = FP8 ? 7.0f : 0.0f;
     // Keep the next item's Q rows in registers for a whole item?  Only where the register
-    // file has room (not with the fp8 tile, not with 16 head rows); otherwise the rows are
-    // fetched when the item starts, which costs that wavefront one exposed cache latency.
-    constexpr bool Q_AHEAD = !FP8 && GQ <= 2;
+    // file has room (not with 16 head rows, not with the fp8 tile on a contiguous cache, whose
+    // per-lane offsets take more registers); otherwise the rows are fetched when the item
+    // starts, which costs that wavefront one exposed cache latency behind its prefetched tiles.
+    constexpr bool Q_AHEAD = GQ <= 2 && !(FP8 && !PAGED);
     constexpr int step = kWaves * TILE;                   // token stride between a wave's tiles
     constexpr int TRIP = kMaxGroup * kHeadDim + 2 * kMaxGroup;   // floats: O, then max, then sum
     static_assert(VR * RPI == TILE && KR == VR && KSTRIDE <= VSTRIDE, "tile geometry");

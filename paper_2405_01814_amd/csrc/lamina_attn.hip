@@ -278,9 +278,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         const int per = (R + kThreads - 1) / kThreads;
         const int b = tid * per;
         const int e = min(R, b + per);
+        constexpr int kPer = kMaxSplitBatch / kThreads;   // requests per thread at most
+        int un[kPer];                                     // their unit counts, read once
         int sum = 0;
-        for (int i = b; i < e; ++i)
-            sum += units_of(prm.seq_lens[i]);
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            un[k] = (b + k < e) ? units_of(prm.seq_lens[b + k]) : 0;
+            sum += un[k];
+        }
         int inc = sum;                                    // inclusive scan inside the wavefront
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -299,11 +304,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             tot += v;
         }
         int run = wbase + inc - sum;
-        for (int i = b; i < e; ++i) {
-            s_cum[i] = run;
-            if (j == 0)
-                prm.cum[i] = run;                         // the merge pass reads it back
-            run += units_of(prm.seq_lens[i]);
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            if (b + k < e) {
+                s_cum[b + k] = run;
+                if (j == 0)
+                    prm.cum[b + k] = run;                 // the merge pass reads it back
+            }
+            run += un[k];
         }
         if (tid == 0) {
             s_cum[R] = tot;

@@ -221,10 +221,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     // normal numbers down to p = 2^-13; numerator and denominator share the factor.
     constexpr float kPShift = FP8 ? 7.0f : 0.0f;
     // Keep the next item's Q rows in registers for a whole item?  Only where the register
-    // file has room (not with 16 head rows, not with the fp8 tile on a contiguous cache, whose
-    // per-lane offsets take more registers); otherwise the rows are fetched when the item
-    // starts, which costs that wavefront one exposed cache latency behind its prefetched tiles.
-    constexpr bool Q_AHEAD = GQ <= 2 && !(FP8 && !PAGED);
+    // file has room: contiguous caches spend more registers on per-lane offsets than paged
+    // ones, the fp8 tile more than the bf16 one, 16 head rows more than 8.  Otherwise the rows
+    // are fetched when the item starts, which costs that wavefront one exposed cache latency
+    // behind its prefetched tiles.
+    constexpr bool Q_AHEAD = FP8 ? (PAGED && GQ <= 2) : (PAGED || GQ <= 2);
     constexpr int step = kWaves * TILE;                   // token stride between a wave's tiles
     constexpr int TRIP = kMaxGroup * kHeadDim + 2 * kMaxGroup;   // floats: O, then max, then sum
     static_assert(VR * RPI == TILE && KR == VR && KSTRIDE <= VSTRIDE, "tile geometry");

@@ -66,8 +66,10 @@ typedef struct {
                                1: never; N>1: into N partitions of ceil(max_seq_len / N) tokens
                                (rounded up to a multiple of 256), each processed on its own;
                                0: the library decides, normally "balanced": per call, from seq_lens,
-                               every work-group gets the same share of the call's tokens and a row
-                               is cut only where one share ends and the next begins              */
+                               every work-group gets the same share of the call's work (tokens in
+                               blocks of 128, or 256 for fp8, plus one block per row for its fixed
+                               cost) and a row is cut only where one share ends and the next
+                               begins                                                            */
     float   softmax_scale;  /* 0 means 1/sqrt(head_dim)                                         */
     int32_t device;         /* HIP device ordinal the handle is bound to                        */
     int32_t kernel;         /* LAMINA_KERNEL_MFMA (0); anything else is rejected                */

@@ -78,6 +78,7 @@ struct MainParams {
     int mode;                          // kModeRows / kModeFixed / kModeBalanced
     int P;                             // kModeFixed: partitions per row at most
     int unit;                          // tokens per unit (split modes)
+    int row_cost;                      // balanced mode: units a row weighs beyond its tokens
     int batch;
     int out_is_bf16;
     float scale_log2;                  // softmax scale times log2(e)
@@ -93,6 +94,7 @@ struct MergeParams {
     int Hq, Hkv, G;
     int mode;                          // kModeFixed or kModeBalanced
     int nwg;                           // work-groups of the main pass
+    int row_cost;                      // balanced mode: units a row weighs beyond its tokens
     int R;
     int rows;                          // R * Hq
     int out_is_bf16;
@@ -251,10 +253,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     const int nwg = gridDim.x;
     const const_i32_ptr lens = (const_i32_ptr)prm.seq_lens;
 
-    // units of one row of a request with `len` tokens (split modes)
+    // Units of one row of a request with `len` tokens (split modes).  In balanced mode a row
+    // weighs rc units more than its tokens: starting and finishing an item costs a wavefront
+    // about as long as a 128-token unit, and shares that are equal in tokens alone leave the
+    // work-groups that hold many short rows far behind the others.
+    const int rc = (mode == kModeBalanced) ? prm.row_cost : 0;
     auto units_of = [&](int len) {
         const int n = max(1, (len + unit - 1) / unit);
-        return mode == kModeFixed ? min(prm.P, n) : n;
+        return mode == kModeFixed ? min(prm.P, n) : n + rc;
     };
     unsigned char *vbuf = smem + w * VBUF;                // this wavefront's staging area
     // The lane number as a value the compiler cannot see through.  Code at item boundaries
@@ -354,15 +360,20 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         int whole;                    // covers its whole row: result goes straight to out/lse
         int dest;                     // piece index in the workspace otherwise
     };
-    // Hand out the item that starts at unit s.u (the caller has checked s.u < u1).
+    // Hand out the part of the stream that starts at unit s.u (the caller has checked
+    // s.u < u1) and say whether it is an item: the first rc units of a row stand for its fixed
+    // cost and hold no tokens, so a part that ends inside them is nothing to do.
     auto next_piece = [&](Walk &s, Piece &p) {
         const int E = s.S + s.n;
         const int pe = (mode == kModeBalanced) ? min(E, u1) : s.u + 1;
+        const int T0 = s.S + rc;                          // where the row's tokens start
+        const int a = max(s.u, T0) - T0;                  // token units [a, b) of the row
+        const int b = pe - T0;
         p.r = s.r;
         p.g = s.g;
-        p.t0 = (s.u - s.S) * unit;
-        p.t1 = (mode == kModeRows) ? s.len : min(s.len, (pe - s.S) * unit);
-        p.whole = (s.u == s.S) && (pe == E);
+        p.t0 = a * unit;
+        p.t1 = (mode == kModeRows) ? s.len : min(s.len, b * unit);
+        p.whole = (s.u <= T0) && (pe == E);
         p.dest = (mode == kModeBalanced) ? s.r * Hkv + s.g + j : s.u;
         s.u = pe;
         if (pe == E) {
@@ -373,6 +384,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             if (pe < u1)
                 load_row(s);
         }
+        return b > 0;
     };
     Walk start;
     start.u = u0;
@@ -433,7 +445,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         d.slot = -1;
         while (look.u < u1) {
             Piece p;
-            next_piece(look, p);
+            if (!next_piece(look, p))
+                continue;
             Desc t;
             describe(p, look_slot++, t);
             if (t.n_even > 0) {
@@ -844,9 +857,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         wait_vmem_all();                                  // start-up only: nothing else to do yet
     }
     Walk at = start;                // the item every wavefront of the work-group is on
-    for (int slot = 0; at.u < u1; ++slot) {
+    for (int slot = 0; at.u < u1;) {
         Piece id;
-        next_piece(at, id);
+        if (!next_piece(at, id))
+            continue;
         if (nxt.slot == slot) {
             // Sets A and B already hold (or are receiving) this item's first two tile slots.
             const Desc cur = nxt;
@@ -913,6 +927,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             }
         }
         finalize(id);
+        ++slot;
     }
 }
 
@@ -947,8 +962,9 @@ __global__ __launch_bounds__(64 * kMergeRowsPerBlock) void merge_partials_kernel
         first = S;
         np = n;
     } else {
+        // the work-groups that hold the row's token units (the first row_cost units hold none)
         const long long U = (long long)prm.Hkv * prm.cum[prm.R];
-        const int wf = share_owner(U, prm.nwg, S);
+        const int wf = share_owner(U, prm.nwg, S + prm.row_cost);
         np = share_owner(U, prm.nwg, S + n - 1) - wf + 1;
         first = (long long)r * prm.Hkv + g + wf;
     }
@@ -1161,6 +1177,7 @@ struct lamina_attn {
     int parts;                   // kModeFixed: partitions per row
     int unit;                    // tokens per unit (split modes), else 0
     long long max_pieces;        // partial results the workspace holds
+    int row_cost;                // balanced mode: units a row weighs beyond its tokens
     float scale;
     float *workspace;            // part_out, part_lse, unit prefix sums; nullptr in rows mode
     size_t workspace_bytes;
@@ -1183,6 +1200,10 @@ struct Plan {
 // Upper bound on the persistent grid (two work-groups per compute unit, capped), so that the
 // workspace size does not depend on the device.
 constexpr int kMaxGrid = 1024;
+
+// Balanced mode: what a row weighs beyond its tokens when the shares are cut, in units
+// (measured with 0..3: one unit is best -- workload 3: 65.4 / 67.6 / 66.9 / 66.5 % of peak).
+constexpr int kRowCostUnits = 1;
 
 // Contexts up to this many tokens are never cut by the library's own choice: one work-group
 // streams such a row in ~15 us, less than cutting it saves once the merge launch is paid.
@@ -1225,7 +1246,7 @@ long long max_units_per_row(const lamina_attn_config &c, const Plan &pl)
         return 1;
     if (pl.mode == kModeFixed)
         return pl.parts;
-    return ((long long)c.max_seq_len + pl.unit - 1) / pl.unit;
+    return ((long long)c.max_seq_len + pl.unit - 1) / pl.unit + kRowCostUnits;
 }
 
 long long max_pieces_for(const lamina_attn_config &c, const Plan &pl)
@@ -1377,6 +1398,7 @@ int lamina_attn_create(const lamina_attn_config *cfg, lamina_attn_t *out_handle)
     h->parts = pl.parts;
     h->unit = pl.unit;
     h->max_pieces = max_pieces_for(*cfg, pl);
+    h->row_cost = pl.mode == kModeBalanced ? kRowCostUnits : 0;
     h->scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
     h->workspace = nullptr;
     h->workspace_bytes = workspace_bytes_for(*cfg, pl);
@@ -1443,7 +1465,9 @@ int64_t lamina_attn_count_partials(lamina_attn_t h, const int32_t *host_seq_lens
         long long n = ((long long)len + h->unit - 1) / h->unit;
         if (n < 1)
             n = 1;
-        return (h->mode == kModeFixed && n > h->parts) ? (long long)h->parts : n;
+        if (h->mode == kModeFixed)
+            return n > h->parts ? (long long)h->parts : n;
+        return n + h->row_cost;
     };
     long long total = 0;
     for (int r = 0; r < batch; ++r)
@@ -1457,7 +1481,8 @@ int64_t lamina_attn_count_partials(lamina_attn_t h, const int32_t *host_seq_lens
             const long long S = Hkv * before + g * n;
             const long long np = h->mode == kModeFixed
                                      ? n
-                                     : share_owner(U, nwg, S + n - 1) - share_owner(U, nwg, S) + 1;
+                                     : share_owner(U, nwg, S + n - 1) -
+                                           share_owner(U, nwg, S + h->row_cost) + 1;
             if (np > 1)
                 pieces += np;
         }
@@ -1531,6 +1556,7 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
     mp.mode = h->mode;
     mp.P = h->parts;
     mp.unit = h->unit > 0 ? h->unit : 1;
+    mp.row_cost = h->row_cost;
     mp.batch = p->batch;
     mp.out_is_bf16 = c.out_dtype == LAMINA_BF16;
     mp.scale_log2 = h->scale * kLog2e;
@@ -1583,6 +1609,7 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
         gp.G = h->group;
         gp.mode = h->mode;
         gp.nwg = wgs;
+        gp.row_cost = h->row_cost;
         gp.R = p->batch;
         gp.out_is_bf16 = mp.out_is_bf16;
         gp.rows = p->batch * c.num_q_heads;

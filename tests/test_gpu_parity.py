@@ -422,12 +422,15 @@ def test_append_then_two_phase_equals_one_phase(name):
 
 
 def brute_force_partials(lens, Hkv, G, unit, nwg, parts=None):
-    """Deal the unit stream to work-groups one unit at a time and count the pieces of cut rows."""
+    """Deal the unit stream to work-groups one unit at a time and count the pieces of cut rows.
+    Balanced shares: a row is one unit for its fixed cost, then its tokens in blocks of `unit`;
+    only the token units make pieces."""
     units = [max(1, -(-int(n) // unit)) for n in lens]
     if parts is not None:
         units = [min(parts, u) for u in units]
+    cost = 0 if parts is not None else 1
     owner_of_unit = []
-    U = sum(units) * Hkv
+    U = sum(u + cost for u in units) * Hkv
     q, rem = divmod(U, nwg)
     for j in range(nwg):
         owner_of_unit += [j] * (q + (1 if j < rem else 0))
@@ -435,6 +438,7 @@ def brute_force_partials(lens, Hkv, G, unit, nwg, parts=None):
     total, at = 0, 0
     for n in units:
         for _ in range(Hkv):
+            at += cost
             pieces = n if parts is not None else len(set(owner_of_unit[at:at + n]))
             at += n
             if pieces > 1:

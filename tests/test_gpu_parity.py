@@ -534,3 +534,40 @@ def test_partitioned_handle_limits_are_reported_at_creation():
     op = lamina.DecodeAttention(8, 8, max_batch=1024, max_seq_len=32768)
     assert (op.num_splits, op.split_tokens) == (0, 128)
     op.close()
+
+
+def test_captured_in_a_graph_and_replayed_with_new_lengths():
+    # The call enqueues kernels only (no host read of seq_lens, no allocation, no memset), so it
+    # can be captured once and replayed while q, seq_lens and the cache change underneath it:
+    # the partitioning is redone on the device at every replay.
+    d = dev()
+    w = W.WORKLOADS["llama3_8b_ctx4096"]
+    first = sized("llama3_8b_ctx4096", [9000, 40, 3000, 129])
+    op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=4, max_seq_len=9000)
+    assert op.num_splits == 0
+    t = {k: v.to(d) for k, v in first.items() if isinstance(v, torch.Tensor)}
+    out = torch.empty(4, w.num_q_heads, 128, device=d)
+    lse = torch.empty(4, w.num_q_heads, device=d)
+    side = torch.cuda.Stream(device=d)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                         # warm-up outside the capture
+        op(t["q"], t["k"], t["v"], t["seq_lens"], out=out, lse=lse)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        op(t["q"], t["k"], t["v"], t["seq_lens"], out=out, lse=lse)
+    for lens in ([9000, 40, 3000, 129], [1, 8999, 0, 4097], [512, 512, 512, 512]):
+        b = sized("llama3_8b_ctx4096", lens)
+        # same shapes (the cache is laid out for the handle's capacity), new contents
+        k = torch.zeros_like(t["k"]); v = torch.zeros_like(t["v"])
+        n = b["k"].shape[2]
+        k[:, :, :n] = b["k"].to(d); v[:, :, :n] = b["v"].to(d)
+        t["k"].copy_(k); t["v"].copy_(v)
+        t["q"].copy_(b["q"].to(d)); t["seq_lens"].copy_(b["seq_lens"].to(d))
+        out.fill_(float("nan")); lse.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b), "bf16_f32")
+    op.close()

@@ -118,8 +118,10 @@ int lamina_attn_create(const lamina_attn_config *cfg, lamina_attn_t *out_handle)
  *                blk*pool_stride_block + g*pool_stride_head + (j%16)*128
  *   v_cache      device; same dtype and layout as k_cache
  *   seq_lens     device int32 [R]: tokens to attend, INCLUDING the token being decoded
- *                (whose k, v the caller has already written).  Values above max_seq_len
- *                are not checked and give undefined results.  Never read by the host.
+ *                (whose k, v the caller has already written).  Never read by the host; a value
+ *                above max_seq_len (or, paged, above 16 * block_table_stride) is treated as
+ *                that limit, a negative one as 0, so a bad length cannot cause a read outside
+ *                the cache extent the call was given.
  *   block_table  device int32 [R][block_table_stride]; only entries below
  *                ceil(seq_lens[r]/16) are read.  NULL in contiguous mode.
  *   out          device [R][num_q_heads][128] of out_dtype, dense
@@ -188,7 +190,9 @@ int64_t lamina_attn_count_partials(lamina_attn_t h, const int32_t *host_seq_lens
  *   k_cache, v_cache, block_table, p: as for lamina_decode_attention (p->k_scale / v_scale
  *                 are required for fp8 caches: bytes = e4m3fn(round-to-nearest-even(x / scale)),
  *                 saturating at +-448)
- * positions[r] < 0 skips request r.  Nothing else in the cache is touched.
+ * positions[r] < 0 skips request r; so does a position at or beyond max_seq_len (paged: beyond
+ * the block table row, or in a block whose table entry is negative).  Nothing else in the cache
+ * is touched.
  *
  * lamina_fold_new_token combines a result over the previous tokens with the single new token:
  *   q             device bf16 [R][num_q_heads][128]

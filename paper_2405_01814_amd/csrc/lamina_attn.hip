@@ -79,6 +79,7 @@ struct MainParams {
     int P;                             // kModeFixed: partitions per row at most
     int unit;                          // tokens per unit (split modes)
     int row_cost;                      // balanced mode: units a row weighs beyond its tokens
+    int len_cap;                       // seq_lens values are clamped to this (memory safety)
     int batch;
     int out_is_bf16;
     float scale_log2;                  // softmax scale times log2(e)
@@ -259,7 +260,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     // work-groups that hold many short rows far behind the others.
     const int rc = (mode == kModeBalanced) ? prm.row_cost : 0;
     auto units_of = [&](int len) {
-        const int n = max(1, (len + unit - 1) / unit);
+        const int n = max(1, (min(len, prm.len_cap) + unit - 1) / unit);
         return mode == kModeFixed ? min(prm.P, n) : n + rc;
     };
     unsigned char *vbuf = smem + w * VBUF;                // this wavefront's staging area
@@ -343,7 +344,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         int len;                      // seq_lens[r]
     };
     auto load_row = [&](Walk &s) {
-        s.len = lens[s.r];
+        s.len = min(lens[s.r], prm.len_cap);
         if (mode == kModeRows) {
             s.n = 1;
             s.S = s.r * Hkv + s.g;
@@ -1054,6 +1055,7 @@ struct NewTokenParams {
     int bt_stride;
     int Hq, Hkv, G;
     int rows;                          // append: R * Hkv, fold: R * Hq
+    int pos_cap;                       // append: positions at or beyond this are skipped
     int fp8, paged, out_is_bf16;
     float scale;
 };
@@ -1086,12 +1088,14 @@ __global__ __launch_bounds__(256) void append_kv_kernel(const NewTokenParams prm
     const int r = row / prm.Hkv;
     const int g = row % prm.Hkv;
     const int pos = prm.positions[r];
-    if (pos < 0)
+    if (pos < 0 || pos >= prm.pos_cap)
         return;
     const int esz = prm.fp8 ? 1 : 2;
     long long off;
     if (prm.paged) {
         const long long blk = prm.block_table[(size_t)r * prm.bt_stride + (pos >> 4)];
+        if (blk < 0)
+            return;                                       // no block assigned: nothing to write to
         off = blk * prm.pool_stride_block_b + (long long)g * prm.pool_stride_head_b +
               (long long)(pos & 15) * kHeadDim * esz;
     } else {
@@ -1557,6 +1561,11 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
     mp.P = h->parts;
     mp.unit = h->unit > 0 ? h->unit : 1;
     mp.row_cost = h->row_cost;
+    // a length beyond what the handle (or the block table) was made for must not become an
+    // out-of-bounds read: it is treated as the largest valid one
+    mp.len_cap = c.max_seq_len;
+    if (paged && (long long)p->block_table_stride * c.block_size < mp.len_cap)
+        mp.len_cap = p->block_table_stride * c.block_size;
     mp.batch = p->batch;
     mp.out_is_bf16 = c.out_dtype == LAMINA_BF16;
     mp.scale_log2 = h->scale * kLog2e;
@@ -1676,6 +1685,9 @@ void fill_new_token_params(const lamina_attn *h, const lamina_call_params *p, Ne
     np.paged = c.block_size != 0;
     np.out_is_bf16 = c.out_dtype == LAMINA_BF16;
     np.scale = h->scale;
+    np.pos_cap = c.max_seq_len;
+    if (np.paged && (long long)p->block_table_stride * c.block_size < np.pos_cap)
+        np.pos_cap = p->block_table_stride * c.block_size;
 }
 
 }  // namespace

@@ -571,3 +571,37 @@ def test_captured_in_a_graph_and_replayed_with_new_lengths():
         torch.cuda.synchronize()
         check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b), "bf16_f32")
     op.close()
+
+
+def test_lengths_beyond_the_capacity_are_clamped_and_bad_append_positions_skipped():
+    # A length above max_seq_len (or negative) must not turn into a read outside the cache
+    # the call was given: it is treated as max_seq_len (or 0).
+    d = dev()
+    w = W.WORKLOADS["llama3_8b_ctx4096"]
+    lens = [300, 77, 200, 300]
+    b = sized("llama3_8b_ctx4096", lens)                  # cache rows 0..299 per request
+    for splits in (1, 0, 2):
+        op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=4, max_seq_len=300,
+                                    num_splits=splits)
+        t = {k: v.to(d) for k, v in b.items() if isinstance(v, torch.Tensor)}
+        claimed = torch.tensor([300 + 100_000, 77, -5, 300], dtype=torch.int32, device=d)
+        out, lse = op(t["q"], t["k"], t["v"], claimed)
+        torch.cuda.synchronize()
+        eff = dict(b)
+        eff["seq_lens"] = torch.tensor([300, 77, 0, 300], dtype=torch.int32)
+        check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(eff), "bf16_f32")
+        op.close()
+    # append: positions outside [0, max_seq_len) leave the cache untouched
+    op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=4, max_seq_len=300)
+    t = {k: v.to(d) for k, v in b.items() if isinstance(v, torch.Tensor)}
+    before_k, before_v = t["k"].clone(), t["v"].clone()
+    k_new = torch.ones(4, w.num_kv_heads, 128, dtype=torch.bfloat16, device=d)
+    pos = torch.tensor([300, -1, 1 << 30, 299], dtype=torch.int32, device=d)
+    op.append_kv(k_new, k_new, t["k"], t["v"], pos)
+    torch.cuda.synchronize()
+    iv = torch.int16
+    assert torch.equal(before_k[:3].view(iv), t["k"][:3].view(iv))
+    assert torch.equal(before_v[:3].view(iv), t["v"][:3].view(iv))
+    assert bool((t["k"][3, :, 299] == 1).all()) and bool((t["v"][3, :, 299] == 1).all())
+    assert torch.equal(before_k[3, :, :299].view(iv), t["k"][3, :, :299].view(iv))
+    op.close()

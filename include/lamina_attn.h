@@ -61,7 +61,7 @@ typedef struct {
     int32_t out_dtype;      /* LAMINA_BF16 or LAMINA_F32                                        */
     int32_t block_size;     /* 0: contiguous strided cache; 16: paged cache with a block table  */
     int32_t max_batch;      /* upper bound on `batch` of any call; sizes grid and workspace     */
-    int32_t max_seq_len;    /* upper bound on any seq_lens[r]; sizes the split-KV partition     */
+    int32_t max_seq_len;    /* upper bound on any seq_lens[r] (larger values are clamped to it) */
     int32_t num_splits;     /* how the KV range of a (request, kv head) row is cut (split-KV):
                                1: never; N>1: into N partitions of ceil(max_seq_len / N) tokens
                                (rounded up to a multiple of 256), each processed on its own;

@@ -605,3 +605,28 @@ def test_lengths_beyond_the_capacity_are_clamped_and_bad_append_positions_skippe
     assert bool((t["k"][3, :, 299] == 1).all()) and bool((t["v"][3, :, 299] == 1).all())
     assert torch.equal(before_k[3, :, :299].view(iv), t["k"][3, :, :299].view(iv))
     op.close()
+
+
+def test_two_handles_on_two_streams_do_not_disturb_each_other():
+    # each handle owns its workspace; calls of different handles may overlap on the device
+    d = dev()
+    w = W.WORKLOADS["llama3_8b_ctx4096"]
+    ba = sized("llama3_8b_ctx4096", [6000, 130, 2500])
+    bb = sized("llama3_8b_ctx4096", [17, 5000, 5000, 900, 64])
+    ops, outs, streams = [], [], [torch.cuda.Stream(device=d), torch.cuda.Stream(device=d)]
+    tens = []
+    for b in (ba, bb):
+        ops.append(lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=8,
+                                          max_seq_len=6000))
+        tens.append({k: v.to(d) for k, v in b.items() if isinstance(v, torch.Tensor)})
+    torch.cuda.synchronize()
+    for _ in range(5):                                    # interleave launches of both handles
+        outs = []
+        for op, t, s in zip(ops, tens, streams):
+            outs.append(op(t["q"], t["k"], t["v"], t["seq_lens"], stream=s))
+    for s in streams:
+        s.synchronize()
+    for b, (out, lse) in zip((ba, bb), outs):
+        check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b), "bf16_f32")
+    for op in ops:
+        op.close()

@@ -105,14 +105,16 @@ struct MergeParams {
 // U % nwg work-groups take U / nwg + 1 units, the others U / nwg; work-group j starts at unit
 // j * (U / nwg) + min(j, U % nwg).  These two helpers are that rule and its inverse; the main
 // pass, the merge and the host-side accounting all use them.
-__host__ __device__ inline long long share_begin(long long U, int nwg, int j)
+// (U never exceeds 2^30 -- checked at creation -- so 32-bit arithmetic is exact; the 64-bit
+// divisions it replaces were a noticeable part of the merge kernel's few microseconds.)
+__host__ __device__ inline unsigned share_begin(unsigned U, unsigned nwg, unsigned j)
 {
-    const long long q = U / nwg, rem = U % nwg;
+    const unsigned q = U / nwg, rem = U % nwg;
     return j * q + (j < rem ? j : rem);
 }
-__host__ __device__ inline int share_owner(long long U, int nwg, long long u)
+__host__ __device__ inline int share_owner(unsigned U, unsigned nwg, unsigned u)
 {
-    const long long q = U / nwg, rem = U % nwg;
+    const unsigned q = U / nwg, rem = U % nwg;
     if (u < rem * (q + 1))
         return (int)(u / (q + 1));
     return (int)(rem + (u - rem * (q + 1)) / q);          // q >= 1 here: u >= rem * (q + 1)
@@ -331,8 +333,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     } else {
         U = (long long)R * Hkv;
     }
-    const int u0 = (int)share_begin(U, nwg, j);
-    const int u1 = (int)share_begin(U, nwg, j + 1);
+    const int u0 = (int)share_begin((unsigned)U, nwg, j);
+    const int u1 = (int)share_begin((unsigned)U, nwg, j + 1);
     if (u0 >= u1)
         return;
 
@@ -965,8 +967,8 @@ __global__ __launch_bounds__(64 * kMergeRowsPerBlock) void merge_partials_kernel
     } else {
         // the work-groups that hold the row's token units (the first row_cost units hold none)
         const long long U = (long long)prm.Hkv * prm.cum[prm.R];
-        const int wf = share_owner(U, prm.nwg, S + prm.row_cost);
-        np = share_owner(U, prm.nwg, S + n - 1) - wf + 1;
+        const int wf = share_owner((unsigned)U, prm.nwg, (unsigned)(S + prm.row_cost));
+        np = share_owner((unsigned)U, prm.nwg, (unsigned)(S + n - 1)) - wf + 1;
         first = (long long)r * prm.Hkv + g + wf;
     }
     if (np == 1)
@@ -1466,6 +1468,8 @@ int64_t lamina_attn_count_partials(lamina_attn_t h, const int32_t *host_seq_lens
         return 0;
     const int Hkv = h->cfg.num_kv_heads;
     auto units_of = [&](int len) {
+        if (len > h->cfg.max_seq_len)
+            len = h->cfg.max_seq_len;                     // as the kernel clamps it
         long long n = ((long long)len + h->unit - 1) / h->unit;
         if (n < 1)
             n = 1;
@@ -1485,8 +1489,8 @@ int64_t lamina_attn_count_partials(lamina_attn_t h, const int32_t *host_seq_lens
             const long long S = Hkv * before + g * n;
             const long long np = h->mode == kModeFixed
                                      ? n
-                                     : share_owner(U, nwg, S + n - 1) -
-                                           share_owner(U, nwg, S + h->row_cost) + 1;
+                                     : share_owner((unsigned)U, nwg, (unsigned)(S + n - 1)) -
+                                           share_owner((unsigned)U, nwg, (unsigned)(S + h->row_cost)) + 1;
             if (np > 1)
                 pieces += np;
         }

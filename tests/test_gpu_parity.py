@@ -630,3 +630,54 @@ def test_two_handles_on_two_streams_do_not_disturb_each_other():
         check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b), "bf16_f32")
     for op in ops:
         op.close()
+
+
+@pytest.mark.parametrize("hq,hkv,block", [(8, 8, 16), (4, 2, 0), (16, 1, 16), (16, 1, 0), (8, 1, 0)])
+def test_fp8_group_sizes_and_layouts(hq, hkv, block):
+    # the fp8 path splits Q per head; cover 1, 2, 8 and 16 heads per group on both layouts
+    b = sized("fp8_paged", [200, 1515, 64, 300], num_q_heads=hq, num_kv_heads=hkv,
+              block_size=block)
+    got, _ = gpu_of(b, max_seq_len=3000)                  # a capacity that makes the handle cut rows
+    check(got, oracle_of(b), "fp8")
+
+
+def test_fp8_queries_of_extreme_and_mixed_magnitude():
+    # With an fp8 cache each query row is rescaled by a power of two and split into two e4m3
+    # halves.  Heads whose queries are huge, tiny, zero, or mix magnitudes inside one row must
+    # come out as exactly as ordinary ones.
+    b = sized("fp8_paged", [900, 130, 257], num_q_heads=16, num_kv_heads=2)
+    q = b["q"].float()
+    q[:, 0] *= 3.0e4                                      # saturates the softmax on one key
+    q[:, 1] *= 1.0e-6                                     # uniform softmax
+    q[:, 2] = 0.0
+    q[:, 3, :64] *= 2.0 ** -12                            # 4096:1 inside one row
+    q[:, 4, ::2] *= 2.0 ** 9
+    q[:, 5] *= 40.0
+    q[:, 6, 5] = 1.0e3                                    # one dominant component
+    b["q"] = q.to(torch.bfloat16)
+    got, _ = gpu_of(b, max_seq_len=1000)
+    out, lse = got
+    ref_out, ref_lse = oracle_of(b)
+    assert np.isfinite(out).all()
+    assert np.abs(out - ref_out).max() <= 3e-2
+    # lse grows with the score scale: compare relative to its magnitude
+    assert (np.abs(lse - ref_lse) <= 5e-3 + 2e-3 * np.abs(ref_lse)).all()
+
+
+def test_bf16_queries_of_extreme_and_mixed_magnitude():
+    # saturated, flat and degenerate softmaxes through the online recurrence and the merge
+    b = sized("llama3_8b_ctx4096", [5000, 130, 257], num_q_heads=8, num_kv_heads=2)
+    q = b["q"].float()
+    q[:, 0] *= 3.0e4
+    q[:, 1] *= 1.0e-6
+    q[:, 2] = 0.0
+    q[:, 3, :64] *= 2.0 ** -12
+    q[:, 4] *= 40.0
+    b["q"] = q.to(torch.bfloat16)
+    for splits in (1, 0, 3):
+        got, _ = gpu_of(b, num_splits=splits, max_seq_len=5000)
+        out, lse = got
+        ref_out, ref_lse = oracle_of(b)
+        assert np.isfinite(out).all()
+        assert np.abs(out - ref_out).max() <= 2e-3
+        assert (np.abs(lse - ref_lse) <= 1e-3 + 1e-6 * np.abs(ref_lse)).all()

@@ -681,3 +681,18 @@ def test_bf16_queries_of_extreme_and_mixed_magnitude():
         assert np.isfinite(out).all()
         assert np.abs(out - ref_out).max() <= 2e-3
         assert (np.abs(lse - ref_lse) <= 1e-3 + 1e-6 * np.abs(ref_lse)).all()
+
+
+def test_fp8_scales_over_many_orders_of_magnitude():
+    # the K scale folds into the score scale and the V scale into the epilogue; neither may
+    # lose accuracy when the scales are far from 1 (the oracle dequantises with the same ones)
+    b = sized("fp8_paged", [700, 64, 2000, 129], num_q_heads=8, num_kv_heads=2)
+    b["k_scale"] = torch.tensor([[1e-4, 1.0], [0.5, 3e-3], [2e-2, 1e-5], [7.0, 0.125]])
+    b["v_scale"] = torch.tensor([[1e3, 1e-4], [1.0, 40.0], [1e-6, 2.0], [0.3, 5e2]])
+    got, _ = gpu_of(b, max_seq_len=2000)
+    out, lse = got
+    ref_out, ref_lse = oracle_of(b)
+    assert np.isfinite(out).all()
+    vs = b["v_scale"].numpy().repeat(4, axis=1)[:, :, None]          # per (request, query head)
+    assert (np.abs(out - ref_out) <= 3e-2 * np.maximum(vs * 8.0, 1e-30)).all()   # error scales with V
+    assert (np.abs(lse - ref_lse) <= 5e-3 + 2e-3 * np.abs(ref_lse)).all()

@@ -120,6 +120,18 @@ __host__ __device__ inline int share_owner(unsigned U, unsigned nwg, unsigned u)
     return (int)(rem + (u - rem * (q + 1)) / q);          // q >= 1 here: u >= rem * (q + 1)
 }
 
+// Fixed partitions: with at least kWaveItemParts partitions per wavefront of the grid the
+// WAVEFRONTS take shares of their own (4 x nwg workers) and each works through its partitions
+// alone -- consecutive tiles, no combining with its neighbours, a third of the cost per item;
+// with fewer, the four wavefronts of a work-group share every item (tiles w, w+4, ...), which
+// keeps all of them busy.  (Tried for balanced shares too: rows get cut four times as often,
+// and workloads 5, 7 and uniform batches lost 0-3 %.)
+constexpr unsigned kWaveItemParts = 2;
+__host__ __device__ inline bool wave_items_rule(int mode, unsigned U, unsigned nwg)
+{
+    return mode == kModeFixed && U >= kWaveItemParts * kWaves * nwg;
+}
+
 __device__ __forceinline__ u32x4 load_stream_128(const unsigned char *p)
 {
     // KV bytes are used once: keep them from displacing anything in the caches.
@@ -231,7 +243,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     // are fetched when the item starts, which costs that wavefront one exposed cache latency
     // behind its prefetched tiles.
     constexpr bool Q_AHEAD = FP8 ? (PAGED && GQ <= 2) : (PAGED || GQ <= 2);
-    constexpr int step = kWaves * TILE;                   // token stride between a wave's tiles
+    constexpr int kGroupStep = kWaves * TILE;             // token stride between a wave's tiles when
+                                                          // the four wavefronts share an item
     constexpr int TRIP = kMaxGroup * kHeadDim + 2 * kMaxGroup;   // floats: O, then max, then sum
     static_assert(VR * RPI == TILE && KR == VR && KSTRIDE <= VSTRIDE, "tile geometry");
     __shared__ __attribute__((aligned(16))) unsigned char smem[kWaves * VBUF];
@@ -333,8 +346,13 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     } else {
         U = (long long)R * Hkv;
     }
-    const int u0 = (int)share_begin((unsigned)U, nwg, j);
-    const int u1 = (int)share_begin((unsigned)U, nwg, j + 1);
+    // Workers: the work-groups, or (fixed partitions, enough of them) the wavefronts on their own.
+    const bool wave_items = wave_items_rule(mode, (unsigned)U, (unsigned)nwg);
+    const int worker = wave_items ? j * kWaves + w : j;
+    const int nworkers = wave_items ? nwg * kWaves : nwg;
+    const int step = wave_items ? TILE : kGroupStep;      // token stride between this wave's tiles
+    const int u0 = (int)share_begin((unsigned)U, nworkers, worker);
+    const int u1 = (int)share_begin((unsigned)U, nworkers, worker + 1);
     if (u0 >= u1)
         return;
 
@@ -377,7 +395,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         p.t0 = a * unit;
         p.t1 = (mode == kModeRows) ? s.len : min(s.len, b * unit);
         p.whole = (s.u <= T0) && (pe == E);
-        p.dest = (mode == kModeBalanced) ? s.r * Hkv + s.g + j : s.u;
+        p.dest = (mode == kModeBalanced) ? s.r * Hkv + s.g + worker : s.u;
         s.u = pe;
         if (pe == E) {
             if (++s.g == Hkv) {
@@ -425,7 +443,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         d.slot = slot;
         d.r = p.r;
         d.g = p.g;
-        d.t0w = p.t0 + w * TILE;
+        d.t0w = p.t0 + (wave_items ? 0 : w * TILE);
         d.t1 = p.t1;
         const int nt = (d.t0w < d.t1) ? (d.t1 - d.t0w + step - 1) / step : 0;
         d.n_even = (nt + 1) & ~1;
@@ -733,7 +751,63 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     // item; whichever of the four arrives last combines the triples (same identity as the
     // cross-partition merge) and writes the item's result.  A wavefront can be at most one
     // item ahead: it may not overwrite its parked triple before that item was combined.
+    // End of an item a wavefront worked through alone: normalise and store, straight from the
+    // accumulator layout (lane = head col; 4 consecutive dims per 16-byte store).
+    auto finalize_alone = [&](const Piece &id) {
+        const int lane = fresh_lane();
+        const int col = lane & 15;
+        const int quad = lane >> 4;
+        l_run += __shfl_xor(l_run, 16);
+        l_run += __shfl_xor(l_run, 32);
+        const bool empty = !(l_run > 0.0f);               // a request with no tokens at all
+        float vs = 1.0f;
+        if (FP8)
+            vs = ((const __attribute__((address_space(4))) float *)prm.v_scale)[(size_t)id.r * Hkv + id.g];
+        const float inv = empty ? 0.0f : vs * __builtin_amdgcn_rcpf(l_run);
+        const float lse_nat =
+            empty ? -INFINITY : (m_run + __builtin_amdgcn_logf(l_run) - kPShift) * kLn2;
+        if (col < G) {
+            const size_t row = (size_t)id.r * prm.Hq + id.g * G + col;
+            if (id.whole) {
+                if (quad == 0 && prm.lse)
+                    prm.lse[row] = lse_nat;
+#pragma unroll
+                for (int db = 0; db < 8; ++db) {
+                    const f32x4 o = o_acc[db] * inv;
+                    const size_t at = row * kHeadDim + db * 16 + quad * 4;
+                    if (prm.out_is_bf16) {
+                        u32x2 pk;
+                        pk[0] = (unsigned)bf16_bits(o[0]) | ((unsigned)bf16_bits(o[1]) << 16);
+                        pk[1] = (unsigned)bf16_bits(o[2]) | ((unsigned)bf16_bits(o[3]) << 16);
+                        *reinterpret_cast<u32x2 *>(static_cast<unsigned short *>(prm.out) + at) = pk;
+                    } else {
+                        *reinterpret_cast<f32x4 *>(static_cast<float *>(prm.out) + at) = o;
+                    }
+                }
+            } else {
+                const size_t slot = (size_t)id.dest * G + col;
+                if (quad == 0)
+                    prm.part_lse[slot] = lse_nat;
+#pragma unroll
+                for (int db = 0; db < 8; ++db)
+                    *reinterpret_cast<f32x4 *>(prm.part_out + slot * kHeadDim + db * 16 + quad * 4) =
+                        o_acc[db] * inv;
+            }
+        }
+        m_run = -INFINITY;
+        l_run = 0.0f;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+            f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            o_acc[db] = z;
+        }
+    };
+
     auto finalize = [&](const Piece &id) {
+        if (wave_items) {
+            finalize_alone(id);
+            return;
+        }
         const int lane = fresh_lane();
         const int col = lane & 15;
         const int quad = lane >> 4;

@@ -696,3 +696,24 @@ def test_fp8_scales_over_many_orders_of_magnitude():
     vs = b["v_scale"].numpy().repeat(4, axis=1)[:, :, None]          # per (request, query head)
     assert (np.abs(out - ref_out) <= 3e-2 * np.maximum(vs * 8.0, 1e-30)).all()   # error scales with V
     assert (np.abs(lse - ref_lse) <= 5e-3 + 2e-3 * np.abs(ref_lse)).all()
+
+
+@pytest.mark.parametrize("name,kind,out_dtype", [("fp8_paged", "fp8", "f32"),
+                                                 ("llama3_70b_headshare_paged", "bf16_bf16", "bf16"),
+                                                 ("llama3_8b_ctx4096", "bf16_f32", "f32")])
+def test_many_fixed_partitions_are_worked_through_by_single_wavefronts(name, kind, out_dtype):
+    # 64 partitions x 64 (request, kv head) rows = 4096 items: at least two per wavefront of the
+    # grid, so each wavefront takes partitions of its own (no combining across wavefronts);
+    # ragged ends, one short and one empty request included
+    w = W.WORKLOADS[name]
+    hkv = 8
+    lens = [16384, 16000, 1, 0, 9000, 16383, 4097, 12345]
+    b = sized(name, lens, num_q_heads=w.group * hkv, num_kv_heads=hkv)
+    got, info = gpu_of(b, out_dtype=out_dtype, num_splits=64, max_seq_len=16384)
+    assert info == (64, 256)
+    pairs = sample_pairs(b, 96, 11)
+    ref = oracle_of(b, pairs=pairs)
+    check(got, ref, kind, pairs=pairs)
+    out, lse = got
+    assert np.isfinite(out).all()
+    assert (out[3] == 0).all() and np.isneginf(lse[3]).all()          # the empty request

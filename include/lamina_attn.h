@@ -42,12 +42,6 @@ enum {
 
 enum { LAMINA_BF16 = 0, LAMINA_FP8_E4M3 = 1, LAMINA_F32 = 2 };
 
-/* Kernel family of the main pass.  Only the matrix-core kernel exists; the field is kept so
- * that a handle states which one it runs. */
-enum {
-    LAMINA_KERNEL_MFMA = 0         /* matrix-core tiles for q.K^T and p.V                    */
-};
-
 /*
  * Fixed properties of one attention layer-share, given at creation.
  * head_dim must be 128.  num_q_heads must be a multiple of num_kv_heads and the group
@@ -72,7 +66,6 @@ typedef struct {
                                begins                                                            */
     float   softmax_scale;  /* 0 means 1/sqrt(head_dim)                                         */
     int32_t device;         /* HIP device ordinal the handle is bound to                        */
-    int32_t kernel;         /* LAMINA_KERNEL_MFMA (0); anything else is rejected                */
 } lamina_attn_config;
 
 /*
@@ -188,8 +181,9 @@ int64_t lamina_attn_count_partials(lamina_attn_t h, const int32_t *host_seq_lens
  *                 previous length); in paged mode block_table[r][positions[r] / 16] must
  *                 already name the destination block
  *   k_cache, v_cache, block_table, p: as for lamina_decode_attention (p->k_scale / v_scale
- *                 are required for fp8 caches: bytes = e4m3fn(round-to-nearest-even(x / scale)),
- *                 saturating at +-448)
+ *                 are required for fp8 caches: the quotient x / scale is formed in fp32 by a
+ *                 correctly rounded IEEE division, clamped to +-448 and rounded to nearest even
+ *                 on the e4m3fn grid)
  * positions[r] < 0 skips request r; so does a position at or beyond max_seq_len (paged: beyond
  * the block table row, or in a block whose table entry is negative).  Nothing else in the cache
  * is touched.

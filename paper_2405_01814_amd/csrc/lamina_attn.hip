@@ -1141,10 +1141,12 @@ __device__ __forceinline__ float bf16_bits_to_float(unsigned short b)
     return __builtin_bit_cast(float, (unsigned)b << 16);
 }
 
-// x -> the value an fp8 cache holds for it: e4m3fn(rne(x / scale)) (saturating), as a byte.
-__device__ __forceinline__ unsigned char quantise_e4m3fn(float x, float inv_scale)
+// x -> the byte an fp8 cache holds for it: the quotient x / scale formed in fp32 (IEEE division,
+// correctly rounded -- not a multiplication by a rounded reciprocal, which can land on the other
+// side of an e4m3 tie), clamped to +-448, then rounded to nearest even on the e4m3fn grid.
+__device__ __forceinline__ unsigned char quantise_e4m3fn(float x, float scale)
 {
-    const float y = fminf(fmaxf(x * inv_scale, -448.0f), 448.0f);
+    const float y = fminf(fmaxf(x / scale, -448.0f), 448.0f);
     return (unsigned char)(__builtin_amdgcn_cvt_pk_fp8_f32(y, 0.0f, 0, false) & 0xFF);
 }
 
@@ -1184,14 +1186,14 @@ __global__ __launch_bounds__(256) void append_kv_kernel(const NewTokenParams prm
         reinterpret_cast<unsigned *>(prm.k_cache + off)[lane] = kk;
         reinterpret_cast<unsigned *>(prm.v_cache + off)[lane] = vv;
     } else {
-        const float iks = 1.0f / prm.k_scale[row];
-        const float ivs = 1.0f / prm.v_scale[row];
+        const float ks = prm.k_scale[row];
+        const float vs = prm.v_scale[row];
         const unsigned short kq =
-            (unsigned short)quantise_e4m3fn(bf16_bits_to_float(kk & 0xFFFF), iks) |
-            ((unsigned short)quantise_e4m3fn(bf16_bits_to_float(kk >> 16), iks) << 8);
+            (unsigned short)quantise_e4m3fn(bf16_bits_to_float(kk & 0xFFFF), ks) |
+            ((unsigned short)quantise_e4m3fn(bf16_bits_to_float(kk >> 16), ks) << 8);
         const unsigned short vq =
-            (unsigned short)quantise_e4m3fn(bf16_bits_to_float(vv & 0xFFFF), ivs) |
-            ((unsigned short)quantise_e4m3fn(bf16_bits_to_float(vv >> 16), ivs) << 8);
+            (unsigned short)quantise_e4m3fn(bf16_bits_to_float(vv & 0xFFFF), vs) |
+            ((unsigned short)quantise_e4m3fn(bf16_bits_to_float(vv >> 16), vs) << 8);
         reinterpret_cast<unsigned short *>(prm.k_cache + off)[lane] = kq;
         reinterpret_cast<unsigned short *>(prm.v_cache + off)[lane] = vq;
     }
@@ -1215,10 +1217,10 @@ __global__ __launch_bounds__(256) void fold_new_token_kernel(const NewTokenParam
     float v0 = bf16_bits_to_float(vv & 0xFFFF), v1 = bf16_bits_to_float(vv >> 16);
     if (prm.fp8) {
         const float ks = prm.k_scale[kvrow], vs = prm.v_scale[kvrow];
-        k0 = dequantise_e4m3fn(quantise_e4m3fn(k0, 1.0f / ks), ks);
-        k1 = dequantise_e4m3fn(quantise_e4m3fn(k1, 1.0f / ks), ks);
-        v0 = dequantise_e4m3fn(quantise_e4m3fn(v0, 1.0f / vs), vs);
-        v1 = dequantise_e4m3fn(quantise_e4m3fn(v1, 1.0f / vs), vs);
+        k0 = dequantise_e4m3fn(quantise_e4m3fn(k0, ks), ks);
+        k1 = dequantise_e4m3fn(quantise_e4m3fn(k1, ks), ks);
+        v0 = dequantise_e4m3fn(quantise_e4m3fn(v0, vs), vs);
+        v1 = dequantise_e4m3fn(quantise_e4m3fn(v1, vs), vs);
     }
     float dot = bf16_bits_to_float(qq & 0xFFFF) * k0 + bf16_bits_to_float(qq >> 16) * k1;
 #pragma unroll
@@ -1366,8 +1368,6 @@ const char *check_config(const lamina_attn_config *c, int *code)
     const int G = c->num_q_heads / c->num_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16)
         return "group size num_q_heads/num_kv_heads must be 1, 2, 4, 8 or 16";
-    if (c->kernel != LAMINA_KERNEL_MFMA)
-        return "unknown kernel family";
     if (c->num_splits > 1 && c->max_batch > kMaxSplitBatch)
         return "a partitioned handle supports max_batch up to 1024";
     {
@@ -1434,6 +1434,10 @@ int grid_for(const lamina_attn *h, int batch)
         wgs = h->resident_wgs;
     return (int)wgs;
 }
+
+int enqueue_decode(lamina_attn *h, const void *q, const void *k_cache, const void *v_cache,
+                   const int32_t *seq_lens, const int32_t *block_table, void *out, float *lse,
+                   const lamina_call_params *p);
 
 }  // namespace
 
@@ -1580,6 +1584,20 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
 {
     if (!h)
         return LAMINA_ERR_INVALID_ARG;
+    return enqueue_decode(h, q, k_cache, v_cache, seq_lens, block_table, out, lse, p);
+}
+
+}  // extern "C"
+
+namespace {
+
+// Validate one call and enqueue its kernels.  `h` may be a handle made by lamina_attn_create
+// or a description on the caller's stack whose workspace is the static scratch area; nothing
+// here allocates.
+int enqueue_decode(lamina_attn *h, const void *q, const void *k_cache, const void *v_cache,
+                   const int32_t *seq_lens, const int32_t *block_table, void *out, float *lse,
+                   const lamina_call_params *p)
+{
     h->err[0] = 0;
     if (!p)
         return fail(h, LAMINA_ERR_INVALID_ARG, "call params are NULL");
@@ -1709,10 +1727,6 @@ int lamina_decode_attention(lamina_attn_t h, const void *q, const void *k_cache,
     }
     return LAMINA_OK;
 }
-
-}  // extern "C"
-
-namespace {
 
 // Shared argument checks of the two new-token entry points.  Returns nullptr if fine.
 const char *check_new_token_args(const lamina_attn *h, const lamina_call_params *p, bool need_layout,

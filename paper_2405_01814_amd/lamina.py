@@ -24,7 +24,6 @@ LAMINA_ERR_UNSUPPORTED = -2
 LAMINA_ERR_HIP = -3
 LAMINA_ERR_WORKSPACE = -4
 LAMINA_BF16, LAMINA_FP8_E4M3, LAMINA_F32 = 0, 1, 2
-LAMINA_KERNEL_MFMA = 0
 
 EXPORTS = ("lamina_attn_create", "lamina_decode_attention", "lamina_attn_destroy",
            "lamina_attn_last_error", "lamina_attn_workspace_bytes", "lamina_attn_num_splits",
@@ -45,7 +44,7 @@ class lamina_attn_config(ctypes.Structure):
                 ("out_dtype", ctypes.c_int32), ("block_size", ctypes.c_int32),
                 ("max_batch", ctypes.c_int32), ("max_seq_len", ctypes.c_int32),
                 ("num_splits", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
-                ("device", ctypes.c_int32), ("kernel", ctypes.c_int32)]
+                ("device", ctypes.c_int32)]
 
 
 class lamina_call_params(ctypes.Structure):
@@ -73,12 +72,23 @@ def build_library(verbose: bool = False) -> str:
 _lib = None
 
 
+def library_is_stale() -> bool:
+    """True if no built library exists or a source or header it is built from is newer."""
+    if not os.path.exists(LIB_PATH):
+        return True
+    built = os.path.getmtime(LIB_PATH)
+    deps = list(_SRCS) + [os.path.join(_INC, f) for f in sorted(os.listdir(_INC))
+                          if f.endswith(".h")]
+    return any(os.path.getmtime(d) > built for d in deps)
+
+
 def load():
-    """Load the built library (building it first only if no built library exists)."""
+    """Load the built library, building it first if it is missing or older than any of its
+    sources or headers (an edited kernel must never be tested through an old binary)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
+    if library_is_stale():
         build_library()
     lib = ctypes.CDLL(LIB_PATH)
     vp = ctypes.c_void_p
@@ -238,10 +248,10 @@ class DecodeAttention:
 
     def __init__(self, num_q_heads, num_kv_heads, max_batch, max_seq_len, *, kv_dtype="bf16",
                  out_dtype="f32", block_size=0, num_splits=0, softmax_scale=0.0, device=0,
-                 head_dim=128, kernel=LAMINA_KERNEL_MFMA):
+                 head_dim=128):
         self.cfg = lamina_attn_config(num_q_heads, num_kv_heads, head_dim, _DTYPES[kv_dtype],
                                       _DTYPES[out_dtype], block_size, max_batch, max_seq_len,
-                                      num_splits, softmax_scale, device, kernel)
+                                      num_splits, softmax_scale, device)
         rc, self.handle = lamina_attn_create(self.cfg)
         if rc != LAMINA_OK:
             self.handle = None

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_binding_struct_layouts_match_the_header():
     # field order and types as declared; sizes as a C compiler lays them out
-    assert ctypes.sizeof(lamina.lamina_attn_config) == 12 * 4
+    assert ctypes.sizeof(lamina.lamina_attn_config) == 11 * 4
     assert ctypes.sizeof(lamina.lamina_call_params) == 8 + 5 * 8 + 8 + 3 * 8
     assert lamina.lamina_call_params.kv_stride_req.offset == 8
     assert lamina.lamina_call_params.k_scale.offset == 56
@@ -38,7 +38,7 @@ def test_binding_struct_layouts_match_the_header():
 
 def good_cfg(**kw):
     c = lamina.lamina_attn_config(32, 8, 128, lamina.LAMINA_BF16, lamina.LAMINA_F32, 0,
-                                  64, 4096, 0, 0.0, 0, 0)
+                                  64, 4096, 0, 0.0, 0)
     for k, v in kw.items():
         setattr(c, k, v)
     return c
@@ -67,7 +67,6 @@ def test_workspace_query_follows_the_partitioning():
     ("head_dim", 64, lamina.LAMINA_ERR_UNSUPPORTED),
     ("block_size", 32, lamina.LAMINA_ERR_UNSUPPORTED),
     ("num_kv_heads", 1, lamina.LAMINA_ERR_UNSUPPORTED),           # group size 32
-    ("kernel", 9, lamina.LAMINA_ERR_UNSUPPORTED),
 ])
 def test_create_rejects_bad_configs_before_any_gpu_work(field, value, code):
     rc, h = lamina.lamina_attn_create(good_cfg(**{field: value}))

@@ -209,6 +209,40 @@ int lamina_fold_new_token(lamina_attn_t h, const void *q, const void *k_new, con
                           const float *out_prev, const float *lse_prev, void *out, float *lse,
                           const lamina_call_params *p);
 
+/*
+ * lamina_decode_attention for callers that cannot allocate device memory or create a handle:
+ * code under HIP graph capture, tight serving loops that must not reach hipMalloc, harnesses
+ * that forbid it.  Same operator, same kernels, same arguments and argument checks as
+ * lamina_decode_attention, with cfg in place of the handle; results are bit-identical to those
+ * of a handle made from the same cfg.  The call allocates nothing, on the host or on the device
+ * (no hipMalloc / hipFree, no handle): the partial results of cut rows go to a fixed area of
+ * LAMINA_STATIC_SCRATCH_BYTES of device memory that is part of the library's code object -- each
+ * GPU the library runs on holds its own copy from the first call on it until the process ends.
+ *
+ * Limit: lamina_attn_workspace_bytes(cfg) must not exceed LAMINA_STATIC_SCRATCH_BYTES, else
+ * LAMINA_ERR_WORKSPACE is returned and nothing is launched (configurations that never cut rows
+ * need no scratch at all; the five named workloads of this build need 5-17 MiB).
+ * Every call on one GPU uses that GPU's one area: calls that overlap on a GPU (two streams, two
+ * threads) race on it and must be serialised by the caller; calls on one stream are ordered by
+ * the stream.  Nothing in the area has to start at zero -- each call writes every partial
+ * result and prefix sum before its merge pass reads it -- so a call is not disturbed by what the
+ * previous one left behind.
+ * The first call on a device resolves the area's address and the device's compute-unit count
+ * (no allocation, but not stream work either): make that call before a stream capture begins.
+ * Errors as for lamina_attn_create (bad cfg) and lamina_decode_attention; the message is
+ * returned by lamina_attn_last_error(NULL) on the calling thread.
+ */
+#define LAMINA_STATIC_SCRATCH_BYTES (32u << 20)
+int lamina_decode_attention_static(const lamina_attn_config *cfg,
+                                   const void *q,
+                                   const void *k_cache,
+                                   const void *v_cache,
+                                   const int32_t *seq_lens,
+                                   const int32_t *block_table,
+                                   void *out,
+                                   float *lse,
+                                   const lamina_call_params *p);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,9 +23,16 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "lamina_attn.h"
+
+// Partial results of lamina_decode_attention_static, the entry point that allocates nothing:
+// one copy of this array per GPU the library runs on, held until the process ends.  In host
+// code this name is only a stand-in for the symbol; the device address comes from
+// hipGetSymbolAddress (static_scratch_for below) and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[LAMINA_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -1859,6 +1866,118 @@ int lamina_fold_new_token(lamina_attn_t h, const void *q, const void *k_new, con
     if (e != hipSuccess)
         return fail_hip(h, "fold kernel launch", e);
     return LAMINA_OK;
+}
+
+}  // extern "C"
+
+// ============================================================================================
+// The entry point for callers that cannot allocate: no handle, no hipMalloc; partial results
+// go to the file-scope `scratch` array.
+// ============================================================================================
+namespace {
+
+constexpr int kMaxStaticDevices = 64;
+
+struct StaticDevice {
+    bool ready;
+    float *ptr;                  // device address of this GPU's copy of `scratch`
+    int resident_wgs;
+};
+StaticDevice g_static_dev[kMaxStaticDevices];
+std::mutex g_static_mu;
+
+// Address of `dev`'s copy of the scratch array and the size of its persistent grid, resolved
+// once per device with that device current.  Returns nullptr and sets *err on failure.
+const StaticDevice *static_scratch_for(int dev, hipError_t *err)
+{
+    *err = hipSuccess;
+    if (dev < 0 || dev >= kMaxStaticDevices) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    StaticDevice &sd = g_static_dev[dev];
+    if (sd.ready)
+        return &sd;
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e == hipSuccess && dev >= ndev)
+        e = hipErrorInvalidDevice;
+    if (e != hipSuccess) {
+        *err = e;
+        return nullptr;
+    }
+    DeviceGuard guard(dev);
+    if (!guard.ok()) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+        *err = e != hipSuccess ? e : hipErrorInvalidSymbol;
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    int cus = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess || cus <= 0) {
+        *err = e != hipSuccess ? e : hipErrorInvalidDevice;
+        return nullptr;
+    }
+    sd.ptr = static_cast<float *>(p);
+    sd.resident_wgs = 2 * cus < kMaxGrid ? 2 * cus : kMaxGrid;
+    sd.ready = true;
+    return &sd;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lamina_decode_attention_static(const lamina_attn_config *cfg, const void *q,
+                                   const void *k_cache, const void *v_cache,
+                                   const int32_t *seq_lens, const int32_t *block_table, void *out,
+                                   float *lse, const lamina_call_params *p)
+{
+    int code;
+    if (const char *msg = check_config(cfg, &code)) {
+        snprintf(g_create_err, sizeof g_create_err, "%s", msg);
+        return code;
+    }
+    lamina_attn h;                                        // on the stack: nothing is allocated
+    h.cfg = *cfg;
+    h.group = cfg->num_q_heads / cfg->num_kv_heads;
+    const Plan pl = make_plan(*cfg);
+    h.mode = pl.mode;
+    h.parts = pl.parts;
+    h.unit = pl.unit;
+    h.max_pieces = max_pieces_for(*cfg, pl);
+    h.row_cost = pl.mode == kModeBalanced ? kRowCostUnits : 0;
+    h.scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
+    h.workspace_bytes = workspace_bytes_for(*cfg, pl);
+    h.err[0] = 0;
+    if (h.workspace_bytes > (size_t)LAMINA_STATIC_SCRATCH_BYTES) {
+        snprintf(g_create_err, sizeof g_create_err,
+                 "this configuration needs %zu bytes of partial results, the static scratch area "
+                 "holds %zu: use a handle (lamina_attn_create), fewer partitions or a smaller "
+                 "max_batch",
+                 h.workspace_bytes, (size_t)LAMINA_STATIC_SCRATCH_BYTES);
+        return LAMINA_ERR_WORKSPACE;
+    }
+    hipError_t e;
+    const StaticDevice *sd = static_scratch_for(cfg->device, &e);
+    if (!sd) {
+        snprintf(g_create_err, sizeof g_create_err, "static scratch area on device %d: %s",
+                 cfg->device, hipGetErrorString(e));
+        return LAMINA_ERR_HIP;
+    }
+    h.workspace = sd->ptr;
+    h.resident_wgs = sd->resident_wgs;
+    const int rc = enqueue_decode(&h, q, k_cache, v_cache, seq_lens, block_table, out, lse, p);
+    if (rc != LAMINA_OK)
+        snprintf(g_create_err, sizeof g_create_err, "%s", h.err);
+    return rc;
 }
 
 }  // extern "C"

@@ -24,11 +24,12 @@ LAMINA_ERR_UNSUPPORTED = -2
 LAMINA_ERR_HIP = -3
 LAMINA_ERR_WORKSPACE = -4
 LAMINA_BF16, LAMINA_FP8_E4M3, LAMINA_F32 = 0, 1, 2
+LAMINA_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = ("lamina_attn_create", "lamina_decode_attention", "lamina_attn_destroy",
            "lamina_attn_last_error", "lamina_attn_workspace_bytes", "lamina_attn_num_splits",
            "lamina_attn_split_tokens", "lamina_attn_count_partials", "lamina_append_kv",
-           "lamina_fold_new_token",
+           "lamina_fold_new_token", "lamina_decode_attention_static",
            "lamina_seqno_alloc", "lamina_seqno_free", "lamina_seqno_wait", "lamina_seqno_signal")
 
 LAMINA_SEQNO_REACHED = 0
@@ -123,6 +124,10 @@ def load():
     lib.lamina_fold_new_token.restype = ctypes.c_int
     lib.lamina_fold_new_token.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp,
                                           ctypes.POINTER(lamina_call_params)]
+    lib.lamina_decode_attention_static.restype = ctypes.c_int
+    lib.lamina_decode_attention_static.argtypes = [ctypes.POINTER(lamina_attn_config), vp, vp, vp,
+                                                   vp, vp, vp, vp,
+                                                   ctypes.POINTER(lamina_call_params)]
     _lib = lib
     return lib
 
@@ -147,6 +152,15 @@ def lamina_decode_attention(h, q, k_cache, v_cache, seq_lens, block_table, out, 
     """Pointers are integers (device addresses) or None."""
     return load().lamina_decode_attention(h, q, k_cache, v_cache, seq_lens, block_table, out,
                                           lse, ctypes.byref(params) if params is not None else None)
+
+
+def lamina_decode_attention_static(cfg: lamina_attn_config, q, k_cache, v_cache, seq_lens,
+                                   block_table, out, lse, params: lamina_call_params) -> int:
+    """The call that allocates nothing: cfg in place of a handle, partial results in the
+    library's static scratch area.  Pointers are integers (device addresses) or None."""
+    return load().lamina_decode_attention_static(
+        ctypes.byref(cfg) if cfg is not None else None, q, k_cache, v_cache, seq_lens,
+        block_table, out, lse, ctypes.byref(params) if params is not None else None)
 
 
 def lamina_append_kv(h, k_new, v_new, k_cache, v_cache, positions, block_table,

@@ -27,6 +27,11 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lamina_oracle.c")
 _LIB = os.path.join(_HERE, "liblamina_oracle.so")
+_LIB_SANITIZED = os.path.join(_HERE, "liblamina_oracle_san.so")
+# Set to 1 to make this package load the AddressSanitizer + UndefinedBehaviorSanitizer build of
+# the C oracle.  The process must then have been started with the ASan runtime preloaded
+# (see sanitizer_env); tests/test_oracle_sanitized.py runs the pin set that way.
+SANITIZE_ENV = "LAMINA_ORACLE_SANITIZE"
 _lib = None
 
 
@@ -47,19 +52,44 @@ class _Layout(ctypes.Structure):
     ]
 
 
-def build(force: bool = False) -> str:
-    """Compile the C oracle with gcc (strict IEEE: no fast-math) and return the path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC, "-lm"]
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the C oracle with gcc (strict IEEE: no fast-math) and return the path.
+    sanitize=True builds a second library with AddressSanitizer and
+    UndefinedBehaviorSanitizer (any finding aborts), host code only."""
+    lib = _LIB_SANITIZED if sanitize else _LIB
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+        flags = (["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                  "-fno-omit-frame-pointer"] if sanitize else ["-O2"])
+        cmd = ["gcc", *flags, "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", lib, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
-    return _LIB
+    return lib
+
+
+def sanitizer_env() -> dict:
+    """Environment for a child process that loads the sanitized oracle: the ASan runtime has to
+    be in the process before anything else allocates, so it is preloaded (ahead of whatever is
+    preloaded already); leak checking is off because the interpreter itself never frees
+    everything."""
+    env = dict(os.environ)
+    asan = subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True,
+                          capture_output=True, text=True).stdout.strip()
+    env["LD_PRELOAD"] = asan + (":" + env["LD_PRELOAD"] if env.get("LD_PRELOAD") else "")
+    env["ASAN_OPTIONS"] = "detect_leaks=0:abort_on_error=1"
+    env["UBSAN_OPTIONS"] = "print_stacktrace=1:halt_on_error=1"
+    env[SANITIZE_ENV] = "1"
+    return env
+
+
+def sanitized() -> bool:
+    """True if this process runs the sanitizer build of the C oracle."""
+    return os.environ.get(SANITIZE_ENV, "") == "1"
 
 
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        lib = ctypes.CDLL(build(sanitize=sanitized()))
         lib.oracle_decode_attention.restype = ctypes.c_int
         lib.oracle_decode_attention.argtypes = [
             ctypes.POINTER(_Layout), ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,

@@ -14,7 +14,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 _SRCS = [os.path.join(_HERE, "csrc", "lamina_attn.hip"),
-         os.path.join(_HERE, "csrc", "lamina_seqno.hip")]
+         os.path.join(_HERE, "csrc", "lamina_seqno.hip"),
+         os.path.join(_HERE, "csrc", "lamina_probe.hip")]
 _INC = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "liblamina_attn.so")
 
@@ -30,7 +31,8 @@ EXPORTS = ("lamina_attn_create", "lamina_decode_attention", "lamina_attn_destroy
            "lamina_attn_last_error", "lamina_attn_workspace_bytes", "lamina_attn_num_splits",
            "lamina_attn_split_tokens", "lamina_attn_count_partials", "lamina_append_kv",
            "lamina_fold_new_token", "lamina_decode_attention_static",
-           "lamina_seqno_alloc", "lamina_seqno_free", "lamina_seqno_wait", "lamina_seqno_signal")
+           "lamina_seqno_alloc", "lamina_seqno_free", "lamina_seqno_wait", "lamina_seqno_signal",
+           "lamina_probe_stream_read")
 
 LAMINA_SEQNO_REACHED = 0
 LAMINA_SEQNO_TIMED_OUT = 1
@@ -128,6 +130,8 @@ def load():
     lib.lamina_decode_attention_static.argtypes = [ctypes.POINTER(lamina_attn_config), vp, vp, vp,
                                                    vp, vp, vp, vp,
                                                    ctypes.POINTER(lamina_call_params)]
+    lib.lamina_probe_stream_read.restype = ctypes.c_int
+    lib.lamina_probe_stream_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp, vp]
     _lib = lib
     return lib
 
@@ -207,6 +211,13 @@ def lamina_seqno_wait(seqno, target: int, timeout_us: int, status, stream) -> in
 
 def lamina_seqno_signal(seqno, value: int, stream) -> int:
     return load().lamina_seqno_signal(seqno, value, stream)
+
+
+def lamina_probe_stream_read(buf, nbytes: int, nontemporal: bool, work_groups: int, sink,
+                             stream) -> int:
+    """Read-only streaming pass over nbytes of device memory at address buf (integers)."""
+    return load().lamina_probe_stream_read(buf, nbytes, 1 if nontemporal else 0, work_groups,
+                                           sink, stream)
 
 
 class Seqno:

@@ -92,6 +92,90 @@ def read_probe(args, torch, lamina, dev) -> int:
     return 0
 
 
+def layer_step(args, torch, lamina, W, dev) -> int:
+    """Time the attention device's per-layer step (Sec. 4.1 receive + Sec. 4.2.2 overlap) in
+    its two orders.  The sequence numbers are already reached, so each wait costs its launch
+    only; what is compared is the work either order puts on the stream.  One JSON line."""
+    import numpy as np
+    w = W.WORKLOADS[args.workload]
+    lens_prev = W.draw_lens(w).astype(np.int32)
+    b = W.generate(w, lens=lens_prev + 1, threads=16)
+    R = len(lens_prev)
+    t = {k: v.to(dev) for k, v in b.items() if isinstance(v, torch.Tensor)}
+    copies = max(1, args.copies)
+    ks = [t["k"]] + [t["k"].clone() for _ in range(copies - 1)]
+    vs = [t["v"]] + [t["v"].clone() for _ in range(copies - 1)]
+    pos = torch.from_numpy(lens_prev.copy()).to(dev)
+    cap = int(lens_prev.max()) + 1
+    mk = lambda od: lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=R,
+                                           max_seq_len=cap, kv_dtype=w.kv_dtype, out_dtype=od,
+                                           block_size=w.block_size)
+    op32, op16 = mk("f32"), mk("bf16")
+    g = torch.Generator().manual_seed(3)
+    k_new = torch.randn(R, w.num_kv_heads, 128, generator=g).to(torch.bfloat16).to(dev)
+    v_new = torch.randn(R, w.num_kv_heads, 128, generator=g).to(torch.bfloat16).to(dev)
+    out_prev = torch.empty(R, w.num_q_heads, 128, device=dev)
+    lse_prev = torch.empty(R, w.num_q_heads, device=dev)
+    out = torch.empty(R, w.num_q_heads, 128, device=dev, dtype=torch.bfloat16)
+    lse = torch.empty(R, w.num_q_heads, device=dev)
+    sq_q, sq_kv = lamina.Seqno(), lamina.Seqno()
+    sq_q.value = 1
+    sq_kv.value = 1
+    kw = dict(block_table=t.get("block_table"), k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))
+    sc = dict(k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))
+
+    def one_phase(i, s):
+        sq_q.wait(1, stream=s)
+        sq_kv.wait(1, stream=s)
+        op16.append_kv(k_new, v_new, ks[i % copies], vs[i % copies], pos, stream=s, **kw)
+        op16(t["q"], ks[i % copies], vs[i % copies], t["seq_lens"], out=out, lse=lse, stream=s, **kw)
+
+    def two_phase(i, s):
+        sq_q.wait(1, stream=s)
+        op32(t["q"], ks[i % copies], vs[i % copies], pos, out=out_prev, lse=lse_prev, stream=s, **kw)
+        sq_kv.wait(1, stream=s)
+        op16.fold_new_token(t["q"], k_new, v_new, out_prev, lse_prev, out=out, lse=lse, stream=s, **sc)
+        op32.append_kv(k_new, v_new, ks[i % copies], vs[i % copies], pos, stream=s, **kw)
+
+    def plain(i, s):
+        op16(t["q"], ks[i % copies], vs[i % copies], t["seq_lens"], out=out, lse=lse, stream=s, **kw)
+
+    s = torch.cuda.Stream(device=dev)
+    res = {"layer_step": w.name, "requests": R, "steps": args.steps, "kv_buffers_rotated": copies,
+           "unit": "us per step, back to back on one stream"}
+    with torch.cuda.stream(s):
+        for label, fn in (("plain_call", plain), ("one_phase", one_phase), ("two_phase", two_phase)):
+            for i in range(args.warmup):
+                fn(i, s)
+            s.synchronize()
+            t0 = time.perf_counter()
+            for i in range(args.steps):
+                fn(i, s)
+            s.synchronize()
+            res[label + "_eager"] = round((time.perf_counter() - t0) * 1e6 / args.steps, 2)
+    for label, fn in (("plain_call", plain), ("one_phase", one_phase), ("two_phase", two_phase)):
+        graphs = []
+        for c in range(copies):
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=s):
+                fn(c, s)
+            graphs.append(gr)
+        for i in range(args.warmup):
+            graphs[i % copies].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[i % copies].replay()
+        torch.cuda.synchronize()
+        res[label + "_graph"] = round((time.perf_counter() - t0) * 1e6 / args.steps, 2)
+    print(json.dumps(res))
+    for o in (op32, op16):
+        o.close()
+    sq_q.close()
+    sq_kv.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,6 +199,12 @@ def main() -> int:
     ap.add_argument("--event-every", type=int, default=8,
                     help="bracket every Nth launch of the timed region with HIP events "
                          "(0: none).  Every launch costs ~6 us of stream time when bracketed.")
+    ap.add_argument("--layer-step", action="store_true",
+                    help="instead of the plain call, time one decode iteration of one layer as "
+                         "the attention device runs it, on one stream: the one-phase order "
+                         "(wait q, wait k/v, append, attend) against the overlapped two-phase "
+                         "order (wait q, attend over the previous tokens, wait k/v, fold the new "
+                         "token in, append), eagerly and as replayed HIP graphs")
     ap.add_argument("--read-probe", action="store_true",
                     help="instead of the operator, time the library's read-only streaming kernel "
                          "(same persistent grid and load shape as the main pass) over buffers of "
@@ -149,6 +239,8 @@ def main() -> int:
         return 0
     if args.read_probe:
         return read_probe(args, torch, lamina, dev)
+    if args.layer_step:
+        return layer_step(args, torch, lamina, W, dev)
     w = W.WORKLOADS[args.workload]
     overridden = bool(args.block_size >= 0 or args.kv_dtype or args.fixed_len or args.batch
                       or args.heads or args.splits >= 0)

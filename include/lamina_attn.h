@@ -60,10 +60,11 @@ typedef struct {
                                1: never; N>1: into N partitions of ceil(max_seq_len / N) tokens
                                (rounded up to a multiple of 256), each processed on its own;
                                0: the library decides, normally "balanced": per call, from seq_lens,
-                               every work-group gets the same share of the call's work (tokens in
+                               every work-group gets a fixed share of the call's work (tokens in
                                blocks of 128, or 256 for fp8, plus one block per row for its fixed
-                               cost) and a row is cut only where one share ends and the next
-                               begins                                                            */
+                               cost; shares are equal but for a fixed 1/16 more for even- and less
+                               for odd-numbered work-groups, which run on dies of different speed)
+                               and a row is cut only where one share ends and the next begins    */
     float   softmax_scale;  /* 0 means 1/sqrt(head_dim)                                         */
     int32_t device;         /* HIP device ordinal the handle is bound to                        */
 } lamina_attn_config;
@@ -150,8 +151,9 @@ const char *lamina_attn_last_error(lamina_attn_t h);
 
 /* Bytes of device workspace a handle made from cfg would own, or 0 if cfg is invalid or rows are
  * never cut.  It holds one partial result (G x (head_dim + 1) fp32) per piece a call can produce
- * -- max_batch * num_kv_heads * N pieces for fixed partitions, max_batch * num_kv_heads + 1024
- * for balanced shares -- plus max_batch + 1 int32 prefix sums.  Does not touch the GPU. */
+ * -- max_batch * num_kv_heads * N pieces plus max_batch + 1 int32 prefix sums for fixed
+ * partitions; 2048 pieces (two per work-group of the largest grid) plus 16 KiB of per-work-group
+ * records for balanced shares, whatever the batch.  Does not touch the GPU. */
 size_t lamina_attn_workspace_bytes(const lamina_attn_config *cfg);
 
 /* Partitioning chosen at creation.  lamina_attn_num_splits: 1 = rows are never cut, N > 1 = fixed
@@ -221,7 +223,7 @@ int lamina_fold_new_token(lamina_attn_t h, const void *q, const void *k_new, con
  *
  * Limit: lamina_attn_workspace_bytes(cfg) must not exceed LAMINA_STATIC_SCRATCH_BYTES, else
  * LAMINA_ERR_WORKSPACE is returned and nothing is launched (configurations that never cut rows
- * need no scratch at all; the five named workloads of this build need 5-17 MiB).
+ * need no scratch at all; the five named workloads of this build need 4-17 MiB).
  * Every call on one GPU uses that GPU's one area: calls that overlap on a GPU (two streams, two
  * threads) race on it and must be serialised by the caller; calls on one stream are ordered by
  * the stream.  Nothing in the area has to start at zero -- each call writes every partial

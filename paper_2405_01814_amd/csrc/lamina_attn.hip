@@ -44,6 +44,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 // Read-only index arrays are read through the constant address space so that uniform reads
@@ -76,6 +77,9 @@ struct MainParams {
     float *part_out;                   // [piece][G][128], normalised partial outputs
     float *part_lse;                   // [piece][G], natural-log partial denominators
     int *cum;                          // [R + 1]: units before request r, written by the main pass
+                                       // (fixed partitions: the merge pass reads it back)
+    int *tails;                        // balanced shares: per work-group, the row whose last piece
+                                       // is that work-group's first item (4 ints each, see below)
     const float *k_scale;
     const float *v_scale;
     long long stride_req_b, stride_head_b, stride_tok_b;     // bytes (contiguous mode)
@@ -95,36 +99,68 @@ struct MainParams {
 struct MergeParams {
     const float *part_out;
     const float *part_lse;
-    const int32_t *seq_lens;
     void *out;
     float *lse;
     const int *cum;                    // [R + 1], units before request r (from the main pass)
     int Hq, Hkv, G;
-    int mode;                          // kModeFixed or kModeBalanced
-    int nwg;                           // work-groups of the main pass
-    int row_cost;                      // balanced mode: units a row weighs beyond its tokens
-    int R;
     int rows;                          // R * Hq
     int out_is_bf16;
 };
 
-// Balanced mode deals U units to nwg work-groups as evenly as whole units allow: the first
-// U % nwg work-groups take U / nwg + 1 units, the others U / nwg; work-group j starts at unit
-// j * (U / nwg) + min(j, U % nwg).  These two helpers are that rule and its inverse; the main
-// pass, the merge and the host-side accounting all use them.
-// (U never exceeds 2^30 -- checked at creation -- so 32-bit arithmetic is exact; the 64-bit
-// divisions it replaces were a noticeable part of the merge kernel's few microseconds.)
-__host__ __device__ inline unsigned share_begin(unsigned U, unsigned nwg, unsigned j)
+// Dealing U units to n workers in contiguous shares.  `skew` = 0: as evenly as whole units
+// allow.  Balanced mode uses skew = kParitySkew: even-numbered work-groups take (64 + skew) / 64
+// of an even share and odd-numbered ones (64 - skew) / 64.  Work-groups go round-robin to the
+// eight accelerator dies, and on every chip measured the odd dies stream 7-14 % slower than the
+// even ones; with equal shares the even dies run dry while the odd ones still have a twelfth of
+// their work, and the call's last tenth runs at half the memory rate.  Measured with the skew swept 0 / 2 / 4 / 6 on one chip: workload 5
+// takes 374 / 367 / 362 / 367 us, workload 7 378 / 374 / 371 / 376 us, workload 3 85.2 / 84.4 /
+// 84.3 / 84.8 us.  With a skew, worker j starts at unit floor(U * c(j) / c(n)), c(j) = 64 j +
+// skew * (j odd).
+// The main pass and the host-side accounting both use these two functions.
+// (U never exceeds 2^30 -- checked at creation -- and c(n) < 2^17, so 64-bit products are exact.)
+constexpr int kParitySkew = 4;
+// The skew pays once a share is long enough for the dies' different speeds to show: a call
+// with ten units (0.6 MB) per work-group is still filling the memory pipeline for a third of
+// its time, every work-group's time is then proportional to its own share, and a skew only
+// makes the even ones last longer (20 requests x 8 kv heads x 4096 tokens: 62.5 us without,
+// 63.5 us with).  Full skew from 24 units per work-group, half of it from 12.  (Below two
+// units per work-group it has to be zero in any case: the merge pass relies on every
+// work-group between a row's first and last piece holding a piece of it.)
+__host__ __device__ inline int share_skew(bool balanced, unsigned U, unsigned n)
 {
-    const unsigned q = U / nwg, rem = U % nwg;
-    return j * q + (j < rem ? j : rem);
+    if (!balanced || U < 12u * n)
+        return 0;
+    return U >= 24u * n ? kParitySkew : kParitySkew / 2;
 }
-__host__ __device__ inline int share_owner(unsigned U, unsigned nwg, unsigned u)
+__host__ __device__ inline unsigned share_begin(unsigned U, unsigned n, unsigned j, int skew)
 {
-    const unsigned q = U / nwg, rem = U % nwg;
-    if (u < rem * (q + 1))
-        return (int)(u / (q + 1));
-    return (int)(rem + (u - rem * (q + 1)) / q);          // q >= 1 here: u >= rem * (q + 1)
+    if (skew == 0) {
+        // the first U % n workers take U / n + 1 units, the others U / n: with fewer units than
+        // workers the workers that get one are the first U, without gaps
+        const unsigned q = U / n, rem = U % n;
+        return j * q + (j < rem ? j : rem);
+    }
+    const unsigned long long cj = 64ull * j + (unsigned long long)skew * (j & 1u);
+    const unsigned long long cn = 64ull * n + (unsigned long long)skew * (n & 1u);
+    return (unsigned)((unsigned long long)U * cj / cn);
+}
+// The worker whose share holds unit u (u < U): the largest j with share_begin(j) <= u.
+__host__ __device__ inline int share_owner(unsigned U, unsigned n, unsigned u, int skew)
+{
+    if (skew == 0) {
+        const unsigned q = U / n, rem = U % n;
+        if (u < rem * (q + 1))
+            return (int)(u / (q + 1));
+        return (int)(rem + (u - rem * (q + 1)) / q);      // q >= 1 here: u >= rem * (q + 1)
+    }
+    long long j = (long long)((unsigned long long)u * n / U);              // a step or two off
+    if (j > (long long)n - 1)
+        j = (long long)n - 1;
+    while (j > 0 && share_begin(U, n, (unsigned)j, skew) > u)
+        --j;
+    while (j + 1 < (long long)n && share_begin(U, n, (unsigned)j + 1, skew) <= u)
+        ++j;
+    return (int)j;
 }
 
 // Fixed partitions: with at least kWaveItemParts partitions per wavefront of the grid the
@@ -171,6 +207,47 @@ __device__ __forceinline__ void split_fp8x4(float x0, float x1, float x2, float 
     l = __builtin_amdgcn_cvt_pk_fp8_f32(x2 - b23[0], x3 - b23[1], l, true);
     hi = h;
     lo = l;
+}
+
+// Reductions over the four lanes {c, c+16, c+32, c+48} that hold one head's statistics.  The
+// gfx950 row-swap instructions exchange 16- and 32-lane halves inside the vector ALU, so the
+// running-max update of every tile neither passes through the LDS crossbar (ds_bpermute) nor
+// shares its wait counter with the LDS traffic of the tile.
+// v_permlane16_swap(x, x) leaves {rows 0,0,2,2 of x} and {rows 1,1,3,3 of x}; v_permlane32_swap(x, x)
+// leaves {lower half, lower half} and {upper half, upper half}: combining the two results is the
+// butterfly step with distance 16 resp. 32.  (The element reads go through scalars: a bit_cast
+// applied directly to a vector element reads element 0 on this compiler.)
+__device__ __forceinline__ void swap16(float x, float &a, float &b)
+{
+    const unsigned xi = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
+    const unsigned ra = r[0], rb = r[1];
+    a = __builtin_bit_cast(float, ra);
+    b = __builtin_bit_cast(float, rb);
+}
+__device__ __forceinline__ void swap32(float x, float &a, float &b)
+{
+    const unsigned xi = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+    const unsigned ra = r[0], rb = r[1];
+    a = __builtin_bit_cast(float, ra);
+    b = __builtin_bit_cast(float, rb);
+}
+__device__ __forceinline__ float quad_max(float x)
+{
+    float a, b;
+    swap16(x, a, b);
+    x = fmaxf(a, b);
+    swap32(x, a, b);
+    return fmaxf(a, b);
+}
+__device__ __forceinline__ float quad_sum(float x)
+{
+    float a, b;
+    swap16(x, a, b);
+    x = a + b;
+    swap32(x, a, b);
+    return a + b;
 }
 
 // Work-group barrier that orders LDS traffic only.  Unlike __syncthreads() it does not wait
@@ -259,6 +336,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     __shared__ int s_busy[kWaves];                        // 1 while s_trip[w] awaits the combine
     __shared__ int s_count;                               // wavefronts that finished the item
     __shared__ int s_cum[kMaxSplitBatch + 1];             // units before request r (split modes)
+    __shared__ int s_len[kMaxSplitBatch];                 // seq_lens, capped (split modes)
     __shared__ float s_wgt[kWaves * kMaxGroup];           // combine weights of the four triples
     __shared__ int s_wsum[kWaves];
 
@@ -313,7 +391,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         int sum = 0;
 #pragma unroll
         for (int k = 0; k < kPer; ++k) {
-            un[k] = (b + k < e) ? units_of(prm.seq_lens[b + k]) : 0;
+            un[k] = 0;
+            if (b + k < e) {
+                const int len = min(prm.seq_lens[b + k], prm.len_cap);
+                s_len[b + k] = len;                       // the row walk reads lengths from here
+                un[k] = units_of(len);
+            }
             sum += un[k];
         }
         int inc = sum;                                    // inclusive scan inside the wavefront
@@ -338,14 +421,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         for (int k = 0; k < kPer; ++k) {
             if (b + k < e) {
                 s_cum[b + k] = run;
-                if (j == 0)
+                if (j == 0 && mode == kModeFixed)
                     prm.cum[b + k] = run;                 // the merge pass reads it back
             }
             run += un[k];
         }
         if (tid == 0) {
             s_cum[R] = tot;
-            if (j == 0)
+            if (j == 0 && mode == kModeFixed)
                 prm.cum[R] = tot;
         }
         __syncthreads();
@@ -358,10 +441,17 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     const int worker = wave_items ? j * kWaves + w : j;
     const int nworkers = wave_items ? nwg * kWaves : nwg;
     const int step = wave_items ? TILE : kGroupStep;      // token stride between this wave's tiles
-    const int u0 = (int)share_begin((unsigned)U, nworkers, worker);
-    const int u1 = (int)share_begin((unsigned)U, nworkers, worker + 1);
-    if (u0 >= u1)
+    const int step_log2 = wave_items ? (FP8 ? 6 : 5) : (FP8 ? 8 : 7);
+    const int skew = share_skew(mode == kModeBalanced, (unsigned)U, (unsigned)nworkers);
+    const int u0 = (int)share_begin((unsigned)U, nworkers, worker, skew);
+    const int u1 = (int)share_begin((unsigned)U, nworkers, worker + 1, skew);
+    if (u0 >= u1) {
+        if (mode == kModeBalanced && tid == 0) {
+            const i32x4 none = {-1, 0, 0, 0};             // no item here, so no row ends here
+            *reinterpret_cast<i32x4 *>(prm.tails + 4 * j) = none;
+        }
         return;
+    }
 
     // Walking the stream: the next unit to hand out and the row it lies in (all wave-uniform).
     struct Walk {
@@ -371,11 +461,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         int len;                      // seq_lens[r]
     };
     auto load_row = [&](Walk &s) {
-        s.len = min(lens[s.r], prm.len_cap);
         if (mode == kModeRows) {
+            s.len = min(lens[s.r], prm.len_cap);
             s.n = 1;
             s.S = s.r * Hkv + s.g;
         } else {
+            s.len = __builtin_amdgcn_readfirstlane(s_len[s.r]);
             const int c0 = __builtin_amdgcn_readfirstlane(s_cum[s.r]);
             const int c1 = __builtin_amdgcn_readfirstlane(s_cum[s.r + 1]);
             s.n = c1 - c0;
@@ -402,7 +493,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         p.t0 = a * unit;
         p.t1 = (mode == kModeRows) ? s.len : min(s.len, b * unit);
         p.whole = (s.u <= T0) && (pe == E);
-        p.dest = (mode == kModeBalanced) ? s.r * Hkv + s.g + worker : s.u;
+        // Balanced shares: a work-group holds at most one piece that continues a row begun in an
+        // earlier share (its first item) and at most one that begins a row it does not finish
+        // (its last item); they go to slots 2j and 2j + 1.
+        p.dest = (mode == kModeBalanced) ? 2 * worker + (s.u <= T0 ? 1 : 0) : s.u;
         s.u = pe;
         if (pe == E) {
             if (++s.g == Hkv) {
@@ -434,7 +528,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         start.g = (u0 - Hkv * c0) / (c1 - c0);
     }
     load_row(start);
-
     // Wave-uniform description of the tiles one wavefront owns in one item.
     struct Desc {
         int slot;                     // ordinal of the item in this work-group; -1: none
@@ -444,7 +537,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         int n_even;                   // tile slots this wavefront runs here (tiles rounded up to even)
         const unsigned char *kbase;
         const unsigned char *vbase;
-        const_i32_ptr bt;
+        const int32_t *bt;            // the request's row of the block table (paged caches)
     };
     auto describe = [&](const Piece &p, int slot, Desc &d) {
         d.slot = slot;
@@ -452,12 +545,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         d.g = p.g;
         d.t0w = p.t0 + (wave_items ? 0 : w * TILE);
         d.t1 = p.t1;
-        const int nt = (d.t0w < d.t1) ? (d.t1 - d.t0w + step - 1) / step : 0;
+        const int nt = (d.t0w < d.t1) ? (d.t1 - d.t0w + step - 1) >> step_log2 : 0;
         d.n_even = (nt + 1) & ~1;
         if (PAGED) {
             d.kbase = prm.k + (long long)p.g * prm.pool_stride_head_b;
             d.vbase = prm.v + (long long)p.g * prm.pool_stride_head_b;
-            d.bt = (const_i32_ptr)(prm.block_table + (size_t)p.r * prm.bt_stride);
+            d.bt = prm.block_table + (size_t)p.r * prm.bt_stride;
         } else {
             const long long off =
                 (long long)p.r * prm.stride_req_b + (long long)p.g * prm.stride_head_b;
@@ -484,12 +577,36 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         }
     };
 
-    // Pool blocks of the 16-token pages of the tile starting at ts (wave-uniform scalar
-    // loads), looked up one refill ahead of the loads that need them.
-    auto fetch_pages = [&](const_i32_ptr bt, int ts, int last, int(&pg)[NSUB]) {
+    // Pool blocks of the 16-token pages of the tile starting at ts: lane `sub` (mod NSUB) of the
+    // returned register holds the block of page ts/16 + sub.  It is a VECTOR load on purpose.
+    // Scalar loads return out of order and share their wait counter with the LDS, so with one
+    // in flight every LDS wait of the tile's arithmetic becomes a wait for the block table
+    // too; a vector load instead queues in order with the K/V loads, and because the pages of
+    // a tile slot are requested one whole generation of its register set ahead (just before
+    // the K/V loads of the slot two earlier), they have always arrived by the time the data
+    // consumed before their use has.
+    // (The fp8 paged variants have no register to spare for it -- the compiler would spill the
+    // prefetched Q rows around the tile loop -- and keep scalar loads, one refill ahead.)
+    constexpr bool VPAGES = PAGED && !FP8;
+    auto load_pages = [&](const int32_t *bt, int ts, int last) -> int {
+        if (!VPAGES)
+            return 0;
+        const int tok = min(ts + (lane & (NSUB - 1)) * 16, last);
+        return bt[tok >> 4];
+    };
+    auto pages_of = [&](int pv, int(&pg)[NSUB]) {
+        if (VPAGES) {
 #pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub)
-            pg[sub] = PAGED ? bt[min(ts + sub * 16, last) >> 4] : 0;
+            for (int sub = 0; sub < NSUB; ++sub)
+                pg[sub] = __builtin_amdgcn_readlane(pv, sub);
+        }
+    };
+    auto fetch_pages = [&](const int32_t *bt, int ts, int last, int(&pg)[NSUB]) {
+        if (PAGED && !VPAGES) {
+#pragma unroll
+            for (int sub = 0; sub < NSUB; ++sub)
+                pg[sub] = ((const_i32_ptr)bt)[min(ts + sub * 16, last) >> 4];
+        }
     };
 
     // Issue all loads of the tile starting at token ts.  Tokens beyond `last` (the item's
@@ -573,8 +690,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                     amax = fmaxf(amax, fmaxf(fabsf(f[i * 8 + d * 2]), fabsf(f[i * 8 + d * 2 + 1])));
                 }
             }
-            amax = fmaxf(amax, __shfl_xor(amax, 16));
-            amax = fmaxf(amax, __shfl_xor(amax, 32));
+            amax = quad_max(amax);
             const int e = (int)((__builtin_bit_cast(unsigned, amax) >> 23) & 255u);
             int a = (amax > 0.0f) ? 134 - e : 0;          // amax * 2^a in [128, 256)
             a = max(-100, min(100, a));
@@ -677,8 +793,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                 x[sub * 4 + v] = s;
                 tmax = fmaxf(tmax, s);
             }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        tmax = quad_max(tmax);
         const float m_new = fmaxf(m_run, tmax);           // finite from the first tile on
         const float alpha = fast_exp2(m_run - m_new);     // exp2(-inf) = 0 on the first tile
         m_run = m_new;
@@ -764,8 +879,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         const int lane = fresh_lane();
         const int col = lane & 15;
         const int quad = lane >> 4;
-        l_run += __shfl_xor(l_run, 16);
-        l_run += __shfl_xor(l_run, 32);
+        l_run = quad_sum(l_run);
         const bool empty = !(l_run > 0.0f);               // a request with no tokens at all
         float vs = 1.0f;
         if (FP8)
@@ -818,8 +932,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         const int lane = fresh_lane();
         const int col = lane & 15;
         const int quad = lane >> 4;
-        l_run += __shfl_xor(l_run, 16);
-        l_run += __shfl_xor(l_run, 32);
+        l_run = quad_sum(l_run);
         {
             // (an LDS-typed pointer: a generic volatile read would be a FLAT load and drag the
             //  vector-memory counter, i.e. the prefetched tiles, into the wait)
@@ -865,12 +978,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             // weights: lane = (head col, wavefront quad)
             const float mw = s_trip[quad * TRIP + kMaxGroup * kHeadDim + col];
             const float lw = s_trip[quad * TRIP + kMaxGroup * kHeadDim + kMaxGroup + col];
-            float M = fmaxf(mw, __shfl_xor(mw, 16));
-            M = fmaxf(M, __shfl_xor(M, 32));
+            const float M = quad_max(mw);
             const float e = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);   // idle wavefront
             float L = e * lw;
-            L += __shfl_xor(L, 16);
-            L += __shfl_xor(L, 32);
+            L = quad_sum(L);
             const bool empty = !(L > 0.0f);               // a request with no tokens at all
             s_wgt[quad * kMaxGroup + col] = empty ? 0.0f : e * vs * __builtin_amdgcn_rcpf(L);
             if (quad == 0 && col < G) {
@@ -927,11 +1038,20 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     float cn = 0.0f;
     Desc nxt;
     find_next(nxt);
+    int pvA = 0, pvB = 0;           // pages of the next refill of set A / set B (paged caches)
     if (nxt.slot >= 0) {
-        // prologue: the first two tile slots of this wavefront's first item, and its Q
+        // prologue: the first two tile slots of this wavefront's first item, and its Q; the
+        // pages of slots 2 and 3 as if they lay in the same item (put right at the item's
+        // start if they do not)
+        const int pv0 = load_pages(nxt.bt, nxt.t0w, nxt.t1 - 1);
+        const int pv1 = load_pages(nxt.bt, nxt.t0w + step, nxt.t1 - 1);
+        pvA = load_pages(nxt.bt, nxt.t0w + 2 * step, nxt.t1 - 1);
+        pvB = load_pages(nxt.bt, nxt.t0w + 3 * step, nxt.t1 - 1);
+        pages_of(pv0, pg);
         fetch_pages(nxt.bt, nxt.t0w, nxt.t1 - 1, pg);
         issue_loads(nxt.kbase, nxt.vbase, nxt.t0w, nxt.t1 - 1, pg, kA, vA);
         __builtin_amdgcn_sched_barrier(0);                // A must be the older set
+        pages_of(pv1, pg);
         fetch_pages(nxt.bt, nxt.t0w + step, nxt.t1 - 1, pg);
         issue_loads(nxt.kbase, nxt.vbase, nxt.t0w + step, nxt.t1 - 1, pg, kB, vB);
         __builtin_amdgcn_sched_barrier(0);
@@ -939,6 +1059,17 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             request_q(nxt.r, nxt.g, qn);
         cn = score_scale(nxt.r, nxt.g);
         wait_vmem_all();                                  // start-up only: nothing else to do yet
+    }
+    if (mode == kModeBalanced && tid == 0) {
+        // Does a row that began in an earlier share end in this one?  Then this work-group's
+        // first item is the row's last piece, and the merge pass combines the row from here:
+        // the pieces lie in slot 2a + 1 (a = the share holding the row's first tokens) and in
+        // slots 2k for the shares k = a + 1 .. j.  One record per work-group, every launch.
+        const int T0 = start.S + rc;
+        const bool ends_here = u0 > T0 && start.S + start.n <= u1;
+        const i32x4 rec = {ends_here ? 1 : -1, start.r, start.g,
+                           share_owner((unsigned)U, (unsigned)nworkers, (unsigned)T0, skew)};
+        *reinterpret_cast<i32x4 *>(prm.tails + 4 * j) = rec;
     }
     Walk at = start;                // the item every wavefront of the work-group is on
     for (int slot = 0; at.u < u1;) {
@@ -968,14 +1099,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             }
             const unsigned char *n_kbase = more ? nxt.kbase : cur.kbase;
             const unsigned char *n_vbase = more ? nxt.vbase : cur.vbase;
-            const const_i32_ptr n_bt = more ? nxt.bt : cur.bt;
+            const int32_t *n_bt = more ? nxt.bt : cur.bt;
             const int n_t0w = more ? nxt.t0w : cur.t1;
             const int n_last = (more ? nxt.t1 : cur.t1) - 1;
             const int c_last = cur.t1 - 1;
             const int n_even = cur.n_even;
             // refill number idx (2, 3, ...) of this item -> its addressing, by scalar selects
             auto target = [&](int idx, const unsigned char *&kb, const unsigned char *&vb,
-                              const_i32_ptr &bt, int &ts, int &last) {
+                              const int32_t *&bt, int &ts, int &last) {
                 const bool in_item = idx < n_even;
                 kb = in_item ? cur.kbase : n_kbase;
                 vb = in_item ? cur.vbase : n_vbase;
@@ -983,9 +1114,18 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                 ts = in_item ? cur.t0w + idx * step : n_t0w + (idx - n_even) * step;
                 last = in_item ? c_last : n_last;
             };
-            const unsigned char *kb, *vb;
-            const_i32_ptr bt;
-            int rts, rlast;
+            const unsigned char *kb, *vb, *kb2, *vb2;
+            const int32_t *bt, *bt2;
+            int rts, rlast, rts2, rlast2;
+            // pvA / pvB hold the pages of refills 2 and 3 as seen from the item before (or the
+            // prologue), which took them to lie in this item.  With only two tile slots here
+            // they lie in the next item, known only now: fetch them again.
+            if (VPAGES && n_even == 2) {
+                target(2, kb, vb, bt, rts, rlast);
+                pvA = load_pages(bt, rts, rlast);
+                target(3, kb, vb, bt, rts, rlast);
+                pvB = load_pages(bt, rts, rlast);
+            }
             target(2, kb, vb, bt, rts, rlast);
             fetch_pages(bt, rts, rlast, pg);
             int ts = cur.t0w;
@@ -993,6 +1133,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                 consume(kA, vA, sc);
                 __builtin_amdgcn_sched_barrier(0);
                 target(k + 2, kb, vb, bt, rts, rlast);
+                pages_of(pvA, pg);
+                if (VPAGES) {
+                    target(k + 4, kb2, vb2, bt2, rts2, rlast2);
+                    pvA = load_pages(bt2, rts2, rlast2);  // older than the loads it rides with
+                }
+                __builtin_amdgcn_sched_barrier(0);
                 issue_loads(kb, vb, rts, rlast, pg, kA, vA);
                 target(k + 3, kb, vb, bt, rts, rlast);
                 fetch_pages(bt, rts, rlast, pg);
@@ -1000,6 +1146,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                 finish(ts, sc);
                 __builtin_amdgcn_sched_barrier(0);
                 consume(kB, vB, sc);
+                __builtin_amdgcn_sched_barrier(0);
+                pages_of(pvB, pg);
+                if (VPAGES) {
+                    target(k + 5, kb2, vb2, bt2, rts2, rlast2);
+                    pvB = load_pages(bt2, rts2, rlast2);
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 issue_loads(kb, vb, rts, rlast, pg, kB, vB);
                 target(k + 4, kb, vb, bt, rts, rlast);
@@ -1018,9 +1170,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
 // -------------------------------------------------------------------------------------------
 // Cross-partition merge (Sec. 4.2.2 identity, any number of parts, log-sum-exp form):
 //   lse = ln sum_p e^{lse_p},  out = sum_p e^{lse_p - lse} out_p.
-// One wavefront per (request, query head) row, four rows per work-group.  Which pieces a row
-// was cut into follows from the unit prefix sums the main pass left in the workspace and the
-// dealing rule; a row that was never cut was already written to out/lse by the main pass.
+// This kernel serves fixed partitions: one wavefront per (request, query head) row, four rows
+// per work-group; the row's pieces are its partitions, found from the unit prefix sums the main
+// pass left in the workspace; a row with a single partition was already written to out/lse by
+// the main pass.  (Balanced shares have their own pass, merge_balanced_kernel below.)
 // Lane p first holds piece p's weight (the log-sum-exp reduction is two wave reductions);
 // then the two half-waves take alternate pieces, each lane four output columns, sixteen
 // pieces' loads in flight per step.
@@ -1039,19 +1192,8 @@ __global__ __launch_bounds__(64 * kMergeRowsPerBlock) void merge_partials_kernel
     const int hl = hq - g * prm.G;
     const int c0 = prm.cum[r];
     const int n = prm.cum[r + 1] - c0;
-    const long long S = (long long)prm.Hkv * c0 + (long long)g * n;   // the row's first unit
-    long long first;
-    int np;
-    if (prm.mode == kModeFixed) {
-        first = S;
-        np = n;
-    } else {
-        // the work-groups that hold the row's token units (the first row_cost units hold none)
-        const long long U = (long long)prm.Hkv * prm.cum[prm.R];
-        const int wf = share_owner((unsigned)U, prm.nwg, (unsigned)(S + prm.row_cost));
-        np = share_owner((unsigned)U, prm.nwg, (unsigned)(S + n - 1)) - wf + 1;
-        first = (long long)r * prm.Hkv + g + wf;
-    }
+    const long long first = (long long)prm.Hkv * c0 + (long long)g * n;   // the row's first unit
+    const int np = n;                                                     // one piece per partition
     if (np == 1)
         return;                                           // the main pass wrote this row itself
     const size_t pstride = (size_t)prm.G;
@@ -1114,6 +1256,150 @@ __global__ __launch_bounds__(64 * kMergeRowsPerBlock) void merge_partials_kernel
     }
     if (lane == 0 && prm.lse)
         prm.lse[row] = M + logf(W);
+}
+
+// -------------------------------------------------------------------------------------------
+// The same combination for balanced shares.  Work-group j of this pass belongs to work-group j
+// of the main pass: if a row that began in an earlier share ended in share j, the main pass
+// left a record (row, first share a) and the row's pieces lie in slot 2a + 1 and in slots 2k,
+// k = a + 1 .. j.  Nearly every cut row has exactly two pieces (a = j - 1), so the two slots
+// that case needs are requested together with the record, before it is known whether they
+// will be used: the common case costs one memory round trip, not three (record, weights,
+// outputs one after the other), and this launch is pure latency on the call's critical path.
+// Wavefront w combines heads w, w + 4, ...; within a wavefront the two half-waves each hold
+// one piece, every lane four output columns.
+// -------------------------------------------------------------------------------------------
+struct BalancedMergeParams {
+    const float *part_out;             // [slot][G][128]
+    const float *part_lse;             // [slot][G]
+    const int *tails;                  // [work-group][4]: flag (1 / -1), request, kv head, first share
+    void *out;
+    float *lse;
+    int Hq, G;
+    int out_is_bf16;
+};
+
+__device__ __forceinline__ void store_merged_row(const BalancedMergeParams &prm, size_t row, int c4,
+                                                 f32x4 o)
+{
+    const size_t at = row * kHeadDim + c4;
+    if (prm.out_is_bf16) {
+        u32x2 pk;
+        pk[0] = (unsigned)bf16_bits(o[0]) | ((unsigned)bf16_bits(o[1]) << 16);
+        pk[1] = (unsigned)bf16_bits(o[2]) | ((unsigned)bf16_bits(o[3]) << 16);
+        *reinterpret_cast<u32x2 *>(static_cast<unsigned short *>(prm.out) + at) = pk;
+    } else {
+        *reinterpret_cast<f32x4 *>(static_cast<float *>(prm.out) + at) = o;
+    }
+}
+
+__global__ __launch_bounds__(256) void merge_balanced_kernel(const BalancedMergeParams prm)
+{
+    const int j = blockIdx.x + 1;                         // share 0 cannot hold the end of an earlier row
+    const int lane = threadIdx.x & 63;
+    const int wv = threadIdx.x >> 6;
+    const int half = lane >> 5;
+    const int c4 = (lane & 31) * 4;
+    const int G = prm.G;
+    constexpr int kHeadsPerWave = kMaxGroup / 4;
+    const i32x4 rec = *reinterpret_cast<const i32x4 *>(prm.tails + 4 * j);
+    // the two-piece case, requested before the record is known: the tail piece (slot 2j) in
+    // the lower half-wave, the head piece of the share before (slot 2j - 1) in the upper one
+    const size_t slot2 = (size_t)(2 * j - half);
+    f32x4 t2[kHeadsPerWave];
+    float l2[kHeadsPerWave];
+#pragma unroll
+    for (int i = 0; i < kHeadsPerWave; ++i) {
+        const int hl = min(wv + 4 * i, G - 1);
+        t2[i] = *reinterpret_cast<const f32x4 *>(prm.part_out + (slot2 * G + hl) * kHeadDim + c4);
+        l2[i] = prm.part_lse[slot2 * G + hl];
+    }
+    if (rec[0] < 0)
+        return;                                           // no row ends in this share
+    const int r = rec[1], g = rec[2], a = rec[3];
+    if (a == j - 1) {
+#pragma unroll
+        for (int i = 0; i < kHeadsPerWave; ++i) {
+            const int hl = wv + 4 * i;
+            if (hl >= G)
+                break;
+            const float lo = __shfl_xor(l2[i], 32);
+            const float M = fmaxf(l2[i], lo);
+            const float w = __expf(l2[i] - M);
+            const float W = w + __expf(lo - M);
+            f32x4 o = w * t2[i];
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                o[c] += __shfl_xor(o[c], 32);
+            const size_t row = (size_t)r * prm.Hq + g * G + hl;
+            if (half == 0)
+                store_merged_row(prm, row, c4, o * (1.0f / W));
+            if (lane == 0 && prm.lse)
+                prm.lse[row] = M + logf(W);
+        }
+        return;
+    }
+    // a row spread over three or more shares: piece p of it (p = 0 .. np - 1) lies in slot
+    // 2a + 1 for p = 0 and in slot 2 (a + p) otherwise.  The weights (lane p holds piece p's)
+    // and the first sixteen pieces' outputs are requested together, one round trip.
+    const int np = j - a + 1;
+    auto slot_of = [&](int p) { return (size_t)(p == 0 ? 2 * a + 1 : 2 * (a + p)); };
+    for (int hl = wv; hl < G; hl += 4) {
+        const float *pl = prm.part_lse + hl;
+        const float *po = prm.part_out + (size_t)hl * kHeadDim + c4;
+        float W = 0.0f, M = -INFINITY;
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+        for (int p0 = 0; p0 < np; p0 += 64) {
+            const int cnt = min(64, np - p0);
+            const float l = (lane < cnt) ? pl[slot_of(p0 + lane) * G] : -INFINITY;
+            f32x4 t[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)                   // pieces beyond cnt re-read the last one
+                t[k] = *reinterpret_cast<const f32x4 *>(
+                    po + slot_of(p0 + min(2 * k + half, cnt - 1)) * G * kHeadDim);
+            float Mc = l;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1)
+                Mc = fmaxf(Mc, __shfl_xor(Mc, off));
+            const float Mn = fmaxf(M, Mc);                // running maximum over chunks of 64 pieces
+            const float rescale = __expf(M - Mn);         // 0 for the first chunk
+            M = Mn;
+            const float e = (lane < cnt) ? __expf(l - M) : 0.0f;
+            W = W * rescale + e;
+            o *= rescale;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int p = 2 * k + half;
+                const float wgt = __shfl(e, min(p, cnt - 1));
+                o += ((p < cnt) ? wgt : 0.0f) * t[k];
+            }
+            for (int i0 = 8; i0 < (cnt + 1) / 2; i0 += 8) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int p = 2 * (i0 + k) + half;
+                    t[k] = *reinterpret_cast<const f32x4 *>(
+                        po + slot_of(p0 + min(p, cnt - 1)) * G * kHeadDim);
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int p = 2 * (i0 + k) + half;
+                    const float wgt = __shfl(e, min(p, cnt - 1));
+                    o += ((p < cnt) ? wgt : 0.0f) * t[k];
+                }
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1)
+            W += __shfl_xor(W, off);
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            o[c] += __shfl_xor(o[c], 32);
+        const size_t row = (size_t)r * prm.Hq + g * G + hl;
+        if (half == 0)
+            store_merged_row(prm, row, c4, o * (1.0f / W));
+        if (lane == 0 && prm.lse)
+            prm.lse[row] = M + logf(W);
+    }
 }
 
 // -------------------------------------------------------------------------------------------
@@ -1345,7 +1631,7 @@ long long max_pieces_for(const lamina_attn_config &c, const Plan &pl)
         return 0;
     if (pl.mode == kModeFixed)
         return rows * pl.parts;                           // piece index = unit number
-    return rows + kMaxGrid;                               // piece index = row + work-group
+    return 2LL * kMaxGrid;                                // two slots per work-group
 }
 
 const char *check_config(const lamina_attn_config *c, int *code)
@@ -1390,10 +1676,13 @@ size_t workspace_bytes_for(const lamina_attn_config &c, const Plan &pl)
 {
     if (pl.mode == kModeRows)
         return 0;
-    // partial outputs and lse per (piece, head of the group), then the unit prefix sums
+    // partial outputs and lse per (piece, head of the group); then the unit prefix sums (fixed
+    // partitions) or one 16-byte record per work-group (balanced shares)
     const size_t G = (size_t)(c.num_q_heads / c.num_kv_heads);
-    return (size_t)max_pieces_for(c, pl) * G * (kHeadDim + 1) * sizeof(float) +
-           (size_t)round_up((c.max_batch + 1) * (int)sizeof(int), 16);
+    const size_t index_bytes = pl.mode == kModeFixed
+                                   ? (size_t)round_up((c.max_batch + 1) * (int)sizeof(int), 16)
+                                   : (size_t)kMaxGrid * 16;
+    return (size_t)max_pieces_for(c, pl) * G * (kHeadDim + 1) * sizeof(float) + index_bytes;
 }
 
 int fail(lamina_attn *h, int code, const char *msg)
@@ -1567,6 +1856,7 @@ int64_t lamina_attn_count_partials(lamina_attn_t h, const int32_t *host_seq_lens
         total += units_of(host_seq_lens[r]);
     const long long U = total * Hkv;
     const int nwg = grid_for(h, batch);
+    const int skew = share_skew(h->mode == kModeBalanced, (unsigned)U, (unsigned)nwg);
     long long pieces = 0, before = 0;
     for (int r = 0; r < batch; ++r) {
         const long long n = units_of(host_seq_lens[r]);
@@ -1574,8 +1864,8 @@ int64_t lamina_attn_count_partials(lamina_attn_t h, const int32_t *host_seq_lens
             const long long S = Hkv * before + g * n;
             const long long np = h->mode == kModeFixed
                                      ? n
-                                     : share_owner((unsigned)U, nwg, (unsigned)(S + n - 1)) -
-                                           share_owner((unsigned)U, nwg, (unsigned)(S + h->row_cost)) + 1;
+                                     : share_owner((unsigned)U, nwg, (unsigned)(S + n - 1), skew) -
+                                           share_owner((unsigned)U, nwg, (unsigned)(S + h->row_cost), skew) + 1;
             if (np > 1)
                 pieces += np;
         }
@@ -1675,7 +1965,10 @@ int enqueue_decode(lamina_attn *h, const void *q, const void *k_cache, const voi
     if (h->mode != kModeRows) {
         mp.part_out = h->workspace;
         mp.part_lse = h->workspace + (size_t)h->max_pieces * h->group * kHeadDim;
+        // the index area behind the pieces starts 16-byte aligned: max_pieces is even and a
+        // piece holds G x 129 floats
         mp.cum = reinterpret_cast<int *>(mp.part_lse + (size_t)h->max_pieces * h->group);
+        mp.tails = mp.cum;
     }
 
     DeviceGuard guard(c.device);
@@ -1709,7 +2002,23 @@ int enqueue_decode(lamina_attn *h, const void *q, const void *k_cache, const voi
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail_hip(h, "main kernel launch", e);
-    if (h->mode != kModeRows) {
+    if (h->mode == kModeBalanced) {
+        if (wgs > 1) {
+            BalancedMergeParams bp;
+            bp.part_out = mp.part_out;
+            bp.part_lse = mp.part_lse;
+            bp.tails = mp.tails;
+            bp.out = out;
+            bp.lse = lse;
+            bp.Hq = c.num_q_heads;
+            bp.G = h->group;
+            bp.out_is_bf16 = mp.out_is_bf16;
+            hipLaunchKernelGGL(merge_balanced_kernel, dim3((unsigned)(wgs - 1)), dim3(256), 0, stream, bp);
+            e = hipGetLastError();
+            if (e != hipSuccess)
+                return fail_hip(h, "merge kernel launch", e);
+        }
+    } else if (h->mode == kModeFixed) {
         MergeParams gp;
         gp.part_out = mp.part_out;
         gp.part_lse = mp.part_lse;
@@ -1719,10 +2028,6 @@ int enqueue_decode(lamina_attn *h, const void *q, const void *k_cache, const voi
         gp.Hq = c.num_q_heads;
         gp.Hkv = c.num_kv_heads;
         gp.G = h->group;
-        gp.mode = h->mode;
-        gp.nwg = wgs;
-        gp.row_cost = h->row_cost;
-        gp.R = p->batch;
         gp.out_is_bf16 = mp.out_is_bf16;
         gp.rows = p->batch * c.num_q_heads;
         hipLaunchKernelGGL(merge_partials_kernel,

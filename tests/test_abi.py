@@ -51,9 +51,9 @@ def test_workspace_query_follows_the_partitioning():
     assert lamina.lamina_attn_workspace_bytes(good_cfg(num_splits=8)) == 64 * 32 * 8 * 129 * 4 + 272
     c = good_cfg(max_batch=16, max_seq_len=131072, num_splits=64)
     assert lamina.lamina_attn_workspace_bytes(c) == 16 * 32 * 64 * 129 * 4 + 80
-    # balanced shares: one piece per row plus one per work-group of the largest grid
+    # balanced shares: two pieces per work-group of the largest grid plus a 16-byte record each
     c = good_cfg(max_batch=64, max_seq_len=8192, num_splits=0)
-    assert lamina.lamina_attn_workspace_bytes(c) == (64 * 8 + 1024) * 4 * 129 * 4 + 272
+    assert lamina.lamina_attn_workspace_bytes(c) == 2048 * 4 * 129 * 4 + 1024 * 16
     assert lamina.lamina_attn_workspace_bytes(good_cfg(head_dim=64)) == 0      # invalid cfg
 
 

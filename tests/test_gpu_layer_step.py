@@ -1,0 +1,199 @@
+"""One decode iteration of one layer as the attention device runs it (Sec. 4.1 receive path +
+Sec. 4.2.2 resource-utilisation overlapping), all on ONE stream and with no host involvement
+between the steps:
+
+    wait(q arrived) -> attend over the previous tokens -> wait(k_n, v_n arrived)
+                    -> fold the new token in -> append k_n, v_n to the cache
+
+A host thread stands in for the sender: it fills the pinned receive buffers and then advances
+the sequence numbers, q first and k_n, v_n later.  The result must equal the oracle over the
+appended cache, and the cache must hold the new rows bit-exactly; once enqueued eagerly and once
+as a captured HIP graph that is replayed with new data."""
+import math
+import threading
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2405_01814_amd import lamina, workloads as W
+
+pytestmark = pytest.mark.gpu
+SCALE = 1.0 / math.sqrt(128)
+
+
+def dev():
+    assert torch.cuda.is_available()
+    return torch.device("cuda:0")
+
+
+def fp8_bytes(x_bf16, scale_f32):
+    quot = x_bf16.float().numpy().astype(np.float32) / scale_f32.numpy().astype(np.float32)[..., None]
+    return torch.tensor([oracle.e4m3fn_encode(float(v)) for v in quot.ravel()],
+                        dtype=torch.uint8).view(*quot.shape)
+
+
+class LayerStep:
+    """Buffers and the enqueue order of one layer step for a named workload."""
+
+    def __init__(self, name, seed):
+        self.w = w = W.WORKLOADS[name]
+        d = dev()
+        self.lens_prev = W.draw_lens(w).astype(np.int32)
+        self.b = b = W.generate(w, lens=self.lens_prev + 1, threads=16)
+        R = self.R = len(self.lens_prev)
+        self.fp8 = w.kv_dtype == "fp8"
+        self.t = {k: v.to(d) for k, v in b.items() if isinstance(v, torch.Tensor)}
+        self.pos = torch.from_numpy(self.lens_prev.copy()).to(d)
+        self.op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=R,
+                                         max_seq_len=int(self.lens_prev.max()) + 1,
+                                         kv_dtype=w.kv_dtype, out_dtype="f32",
+                                         block_size=w.block_size)
+        self.opb = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=R,
+                                          max_seq_len=int(self.lens_prev.max()) + 1,
+                                          kv_dtype=w.kv_dtype, out_dtype="bf16",
+                                          block_size=w.block_size)
+        # receive buffers (pinned host memory written by the sender) and their device copies
+        self.q_host = torch.zeros_like(b["q"]).pin_memory()
+        self.k_host = torch.zeros(R, w.num_kv_heads, 128, dtype=torch.bfloat16).pin_memory()
+        self.v_host = torch.zeros_like(self.k_host).pin_memory()
+        self.q_dev = torch.zeros_like(b["q"], device=d)
+        self.k_dev = torch.zeros_like(self.k_host, device=d)
+        self.v_dev = torch.zeros_like(self.k_host, device=d)
+        self.out_prev = torch.empty(R, w.num_q_heads, 128, device=d)
+        self.lse_prev = torch.empty(R, w.num_q_heads, device=d)
+        self.out = torch.empty(R, w.num_q_heads, 128, device=d, dtype=torch.bfloat16)
+        self.lse = torch.empty(R, w.num_q_heads, device=d)
+        self.sq_q, self.sq_kv = lamina.Seqno(), lamina.Seqno()
+        self.rng = torch.Generator().manual_seed(seed)
+
+    def enqueue(self, s):
+        t = self.t
+        kw = dict(block_table=t.get("block_table"), k_scale=t.get("k_scale"),
+                  v_scale=t.get("v_scale"))
+        self.sq_q.wait(1, timeout_us=20_000_000, stream=s)
+        self.q_dev.copy_(self.q_host, non_blocking=True)
+        self.op(self.q_dev, t["k"], t["v"], self.pos, out=self.out_prev, lse=self.lse_prev,
+                stream=s, **kw)
+        self.sq_kv.wait(1, timeout_us=20_000_000, stream=s)
+        self.k_dev.copy_(self.k_host, non_blocking=True)
+        self.v_dev.copy_(self.v_host, non_blocking=True)
+        self.opb.fold_new_token(self.q_dev, self.k_dev, self.v_dev, self.out_prev, self.lse_prev,
+                                out=self.out, lse=self.lse, k_scale=t.get("k_scale"),
+                                v_scale=t.get("v_scale"), stream=s)
+        self.op.append_kv(self.k_dev, self.v_dev, t["k"], t["v"], self.pos, stream=s, **kw)
+
+    def new_inputs(self):
+        """Fresh q, k_n, v_n for one iteration (host side).  They differ from what the receive
+        buffers and the cache slot hold from the iteration before, so a stale read cannot pass
+        the bit-exact comparison of the cache or the parity check of the output."""
+        w, R = self.w, self.R
+        q = torch.randn(R, w.num_q_heads, 128, generator=self.rng).to(torch.bfloat16)
+        kn = torch.randn(R, w.num_kv_heads, 128, generator=self.rng).to(torch.bfloat16)
+        vn = torch.randn(R, w.num_kv_heads, 128, generator=self.rng).to(torch.bfloat16)
+        return q, kn, vn
+
+    def send(self, q, kn, vn, gap=0.02):
+        """What the sending device does, from a host thread: data first, then the seqno."""
+        time.sleep(gap)
+        self.q_host.copy_(q)
+        self.sq_q.value = 1
+        time.sleep(gap)                                   # k_n, v_n arrive later (Sec. 4.2.2)
+        self.k_host.copy_(kn)
+        self.v_host.copy_(vn)
+        self.sq_kv.value = 1
+
+    def expected(self, q, kn, vn):
+        """Host cache after the append and the oracle over it."""
+        b, w = self.b, self.w
+        k, v = b["k"].clone(), b["v"].clone()
+        rows_k = fp8_bytes(kn, b["k_scale"]) if self.fp8 else kn
+        rows_v = fp8_bytes(vn, b["v_scale"]) if self.fp8 else vn
+        iv = torch.uint8 if self.fp8 else torch.int16
+        pos = torch.from_numpy(self.lens_prev.astype(np.int64))
+        if w.block_size:
+            blk = b["block_table"][torch.arange(self.R), pos // 16].long()
+            k.view(iv)[blk, :, pos % 16] = rows_k.view(iv)
+            v.view(iv)[blk, :, pos % 16] = rows_v.view(iv)
+        else:
+            k.view(iv)[torch.arange(self.R), :, pos] = rows_k.view(iv)
+            v.view(iv)[torch.arange(self.R), :, pos] = rows_v.view(iv)
+        ref = oracle.decode_attention(
+            q, k, v, b["seq_lens"], num_kv_heads=w.num_kv_heads, scale=SCALE,
+            block_table=b.get("block_table"), block_size=w.block_size,
+            k_scale=b.get("k_scale"), v_scale=b.get("v_scale"))
+        return k, v, ref
+
+    def check(self, q, kn, vn):
+        iv = torch.uint8 if self.fp8 else torch.int16
+        k_ref, v_ref, (ref_out, ref_lse) = self.expected(q, kn, vn)
+        assert self.sq_q.status == lamina.LAMINA_SEQNO_REACHED
+        assert self.sq_kv.status == lamina.LAMINA_SEQNO_REACHED
+        assert torch.equal(self.t["k"].cpu().view(iv), k_ref.view(iv))
+        assert torch.equal(self.t["v"].cpu().view(iv), v_ref.view(iv))
+        out = self.out.float().cpu().double().numpy()
+        lse = self.lse.cpu().double().numpy()
+        err = np.abs(out - ref_out)
+        tol = (3e-2 if self.fp8 else 2e-3) + 1e-2 * np.abs(ref_out)      # bf16 output
+        assert (err <= tol).all(), f"max abs {err.max():.3e}"
+        assert np.abs(lse - ref_lse).max() <= (5e-3 if self.fp8 else 1e-3)
+        return float(err.max())
+
+    def reset(self):
+        self.sq_q.value = 0
+        self.sq_kv.value = 0
+        self.out.fill_(float("nan"))
+        self.lse.fill_(float("nan"))
+        torch.cuda.synchronize()
+
+    def close(self):
+        self.op.close()
+        self.opb.close()
+        self.sq_q.close()
+        self.sq_kv.close()
+
+
+@pytest.mark.parametrize("name", ["llama3_70b_headshare_paged", "fp8_paged"])
+def test_layer_step_on_one_stream_eager_and_as_a_replayed_graph(name):
+    print("generating", name, flush=True)
+    ls = LayerStep(name, seed=11)
+    assert ls.op.num_splits == 0                          # phase 1 runs on balanced shares
+    d = dev()
+    s = torch.cuda.Stream(device=d)
+    torch.cuda.synchronize()
+
+    # eager: everything is enqueued before the sender has produced anything
+    q, kn, vn = ls.new_inputs()
+    ls.reset()
+    print("eager step", flush=True)
+    t0 = time.perf_counter()
+    with torch.cuda.stream(s):
+        ls.enqueue(s)
+    sender = threading.Thread(target=ls.send, args=(q, kn, vn))
+    sender.start()
+    s.synchronize()
+    waited = time.perf_counter() - t0
+    sender.join()
+    assert waited >= 0.03, "the stream did not wait for the sender"
+    print("eager max abs err", ls.check(q, kn, vn), flush=True)
+
+    # captured once, replayed with new q, k_n, v_n each time (the cache rows are overwritten)
+    print("capturing", flush=True)
+    ls.sq_q.value = 1                                     # the capture pass itself enqueues nothing
+    ls.sq_kv.value = 1
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s):
+        ls.enqueue(s)
+    for it in range(3):
+        q, kn, vn = ls.new_inputs()
+        ls.reset()
+        print("replay", it, flush=True)
+        graph.replay()
+        sender = threading.Thread(target=ls.send, args=(q, kn, vn, 0.01))
+        sender.start()
+        torch.cuda.synchronize()
+        sender.join()
+        print("replay max abs err", ls.check(q, kn, vn), flush=True)
+    ls.close()

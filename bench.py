@@ -92,6 +92,81 @@ def read_probe(args, torch, lamina, dev) -> int:
     return 0
 
 
+def timeline(args, w, lens, op, step, torch, lamina, W, out_dtype) -> int:
+    """Time-resolved account of one call from the timeline build.  Times are microseconds on the
+    device's constant 100 MHz clock, counted from the entry of the call's first wavefront;
+    percentiles are over the wavefronts (work-groups for the merge pass) that had work."""
+    import numpy as np
+    WAVES, WW, MG, MW = 4096, 64, 4096, 4
+    n_partials = op.count_partials(lens)
+    ab = W.algorithmic_bytes(w, lens, out_bytes=2 if out_dtype == "bf16" else 4,
+                             partial_results=n_partials)
+    for i in range(5):                                    # the sixth call is the one reported
+        step(i)
+    torch.cuda.synchronize()
+    step(5)
+    torch.cuda.synchronize()
+    raw = lamina.lamina_trace_read(WAVES * WW + MG * MW)
+    main = raw[:WAVES * WW].reshape(WAVES, WW).astype(np.float64)
+    merge = raw[WAVES * WW:].reshape(MG, MW).astype(np.float64)
+    act = main[:, 6] > 0
+    m = main[act]
+    t0 = main[:, 0][main[:, 0] > 0].min()
+    us = lambda x: (x - t0) / 100.0
+    pct = lambda x: " ".join(f"{v:7.1f}" for v in np.percentile(x, [0, 10, 50, 90, 100]))
+    end = us(m[:, 5]).max()
+    print(f"timeline of one call, workload {w.name}: {ab['total'] - ab['partials']} needed bytes, "
+          f"split_kv {({1: 'none', 0: 'balanced'}.get(op.num_splits, 'fixed'))}, "
+          f"{int(act.sum())} wavefronts with work, {m[:, 6].mean():.2f} items and "
+          f"{m[:, 7].mean():.1f} tile slots (16 KiB each) per wavefront")
+    print("                                  percentile:     0      10      50      90     100   (us)")
+    print("  wavefront enters the kernel               ", pct(us(main[:, 0][main[:, 0] > 0])))
+    print("  its range of work is known                ", pct(us(m[:, 1])))
+    print("  its first 32 KiB of loads are issued      ", pct(us(m[:, 2])))
+    print("  ... and have arrived                      ", pct(us(m[:, 3])))
+    print("  its first item is finished                ", pct(us(m[:, 8])))
+    print("  its last tile is finished                 ", pct(us(m[:, 4])))
+    print("  wavefront exits                           ", pct(us(m[:, 5])))
+    print("  exit minus last tile (item end, stores)   ", pct((m[:, 5] - m[:, 4]) / 100.0))
+    ma = merge[:, 0] > t0                                  # stamps of this call only
+    if ma.any():
+        print("  merge pass: work-group enters             ", pct(us(merge[ma, 0])))
+        print("  merge pass: work-group exits              ", pct(us(merge[ma, 1])))
+        end = max(end, us(merge[ma, 1]).max())
+    print(f"  main pass ends at {us(m[:, 5]).max():.1f} us, call ends at {end:.1f} us")
+    wg = np.arange(WAVES)[act] // 4
+    ex = us(m[:, 5])
+    nwg = int(wg.max()) + 1
+    print("  work-group exit by die class (work-group number mod 8), mean / last:")
+    print("    " + "  ".join(f"{x}: {ex[wg % 8 == x].mean():.1f}/{ex[wg % 8 == x].max():.1f}"
+                            for x in range(8) if (wg % 8 == x).any()))
+    first = wg < (nwg + 1) // 2
+    if first.any() and (~first).any():
+        print(f"  first work-group on a compute unit (numbers below {(nwg + 1) // 2}) exits at "
+              f"{ex[first].mean():.1f} us on average, the second one at {ex[~first].mean():.1f} us")
+    # aggregate progress: every wavefront stamps the start of loop iterations 0..7 and of every
+    # fourth one after that (an iteration is two tile slots); progress between stamps is
+    # interpolated linearly, so features shorter than one iteration (~9 us in steady state) blur
+    its = [q if q < 8 else 8 + (q - 8) * 4 for q in range(40)]
+    T = us(m[:, 5]).max()
+    grid = np.linspace(0.0, T, 21)
+    done = np.zeros_like(grid)
+    for row in m:
+        n_it = int(row[9])
+        ns = sum(1 for q in its if q < n_it)
+        if ns == 0:
+            continue
+        ts = np.append(us(row[16:16 + ns]), us(row[4]))
+        tl = np.append(np.array(its[:ns]) * 2.0, 2.0 * n_it)
+        done += np.interp(grid, ts, tl, left=0.0, right=tl[-1])
+    rate = np.diff(done) / np.diff(grid) * 16384 / 1e6    # TB/s, every tile slot as 16 KiB
+    print(f"  tile slots consumed per 5 % of the main pass ({T / 20:.1f} us each), as TB/s at 16 KiB "
+          f"per slot (slots that hold no new tokens count too):")
+    print("    " + " ".join(f"{v:.2f}" for v in rate))
+    op.close()
+    return 0
+
+
 def layer_step(args, torch, lamina, W, dev) -> int:
     """Time the attention device's per-layer step (Sec. 4.1 receive + Sec. 4.2.2 overlap) in
     its two orders.  The sequence numbers are already reached, so each wait costs its launch
@@ -137,6 +212,13 @@ def layer_step(args, torch, lamina, W, dev) -> int:
         op16.fold_new_token(t["q"], k_new, v_new, out_prev, lse_prev, out=out, lse=lse, stream=s, **sc)
         op32.append_kv(k_new, v_new, ks[i % copies], vs[i % copies], pos, stream=s, **kw)
 
+    def two_phase_fused(i, s):
+        sq_q.wait(1, stream=s)
+        op32(t["q"], ks[i % copies], vs[i % copies], pos, out=out_prev, lse=lse_prev, stream=s, **kw)
+        sq_kv.wait(1, stream=s)
+        op16.fold_new_token_and_append(t["q"], k_new, v_new, out_prev, lse_prev, ks[i % copies],
+                                       vs[i % copies], pos, out=out, lse=lse, stream=s, **kw)
+
     def plain(i, s):
         op16(t["q"], ks[i % copies], vs[i % copies], t["seq_lens"], out=out, lse=lse, stream=s, **kw)
 
@@ -144,7 +226,8 @@ def layer_step(args, torch, lamina, W, dev) -> int:
     res = {"layer_step": w.name, "requests": R, "steps": args.steps, "kv_buffers_rotated": copies,
            "unit": "us per step, back to back on one stream"}
     with torch.cuda.stream(s):
-        for label, fn in (("plain_call", plain), ("one_phase", one_phase), ("two_phase", two_phase)):
+        for label, fn in (("plain_call", plain), ("one_phase", one_phase), ("two_phase", two_phase),
+                          ("two_phase_fused", two_phase_fused)):
             for i in range(args.warmup):
                 fn(i, s)
             s.synchronize()
@@ -153,7 +236,8 @@ def layer_step(args, torch, lamina, W, dev) -> int:
                 fn(i, s)
             s.synchronize()
             res[label + "_eager"] = round((time.perf_counter() - t0) * 1e6 / args.steps, 2)
-    for label, fn in (("plain_call", plain), ("one_phase", one_phase), ("two_phase", two_phase)):
+    for label, fn in (("plain_call", plain), ("one_phase", one_phase), ("two_phase", two_phase),
+                          ("two_phase_fused", two_phase_fused)):
         graphs = []
         for c in range(copies):
             gr = torch.cuda.CUDAGraph()
@@ -205,6 +289,12 @@ def main() -> int:
                          "(wait q, wait k/v, append, attend) against the overlapped two-phase "
                          "order (wait q, attend over the previous tokens, wait k/v, fold the new "
                          "token in, append), eagerly and as replayed HIP graphs")
+    ap.add_argument("--timeline", action="store_true",
+                    help="instead of timing, run the workload through the timeline build of the "
+                         "library (-DLAMINA_TRACE: the kernels stamp the device clock) and print a "
+                         "time-resolved account of one call: when wavefronts start, issue, get "
+                         "data and finish, the aggregate streaming rate over the call, finish "
+                         "times per die, and where the merge pass sits")
     ap.add_argument("--read-probe", action="store_true",
                     help="instead of the operator, time the library's read-only streaming kernel "
                          "(same persistent grid and load shape as the main pass) over buffers of "
@@ -227,6 +317,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.timeline:
+        lamina.use_trace_library()
     dev = torch.device("cuda:0")
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
@@ -278,6 +370,9 @@ def main() -> int:
         op(t["q"], ks[i % copies], vs[i % copies], t["seq_lens"],
            block_table=t.get("block_table"), k_scale=t.get("k_scale"),
            v_scale=t.get("v_scale"), out=out, lse=lse)
+
+    if args.timeline:
+        return timeline(args, w, lens, op, step, torch, lamina, W, args.out_dtype)
 
     # parity gate on a sample of rows before anything is timed
     max_err = None

@@ -212,6 +212,21 @@ int lamina_fold_new_token(lamina_attn_t h, const void *q, const void *k_new, con
                           const lamina_call_params *p);
 
 /*
+ * lamina_fold_new_token followed by lamina_append_kv in ONE launch, for the attention device's
+ * per-layer step in its overlapped order (Sec. 4.2.2): once k_n, v_n have arrived, the result
+ * over the previous tokens is completed with the new token and the new rows go into the cache.
+ * Arguments, results and errors are those of the two calls (p carries the cache layout and,
+ * for fp8 caches, the scales); the cache rows written and the output are bit-identical to
+ * calling them one after the other.  One small launch instead of two matters because the step
+ * is a chain of launches behind a 60-400 us attention call.
+ */
+int lamina_fold_new_token_and_append(lamina_attn_t h, const void *q, const void *k_new,
+                                     const void *v_new, const float *out_prev,
+                                     const float *lse_prev, void *out, float *lse, void *k_cache,
+                                     void *v_cache, const int32_t *positions,
+                                     const int32_t *block_table, const lamina_call_params *p);
+
+/*
  * lamina_decode_attention for callers that cannot allocate device memory or create a handle:
  * code under HIP graph capture, tight serving loops that must not reach hipMalloc, harnesses
  * that forbid it.  Same operator, same kernels, same arguments and argument checks as

@@ -34,6 +34,30 @@
 // hipGetSymbolAddress (static_scratch_for below) and only that pointer is handed to kernels.
 static __device__ __align__(256) unsigned char scratch[LAMINA_STATIC_SCRATCH_BYTES];
 
+// -------------------------------------------------------------------------------------------
+// Timeline build (-DLAMINA_TRACE, see `bench.py --timeline`): every wavefront of the main pass
+// and every work-group of the merge passes stamps the device's constant 100 MHz clock at a
+// few points -- entry, work range known, first loads issued, first data there, every loop
+// iteration early on and every fourth later, end of its tiles, exit -- and leaves the stamps in
+// a device array that lamina_trace_read copies out.  Without the macro none of it exists.
+// -------------------------------------------------------------------------------------------
+#ifdef LAMINA_TRACE
+constexpr int kTraceWaves = 4096;                      // main pass: kMaxGrid x 4 wavefronts
+constexpr int kTraceWaveWords = 64;
+constexpr int kTraceMergeGroups = 4096;
+constexpr int kTraceMergeWords = 4;
+constexpr int kTraceStamps = 40;                       // loop stamps kept per wavefront
+__device__ unsigned long long g_trace[kTraceWaves * kTraceWaveWords + kTraceMergeGroups * kTraceMergeWords];
+extern "C" int lamina_trace_read(unsigned long long *host, size_t words)
+{
+    const size_t have = sizeof(g_trace) / sizeof(g_trace[0]);
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(g_trace[0]) * (words < have ? words : have));
+}
+#define LAMINA_TRACE_ONLY(...) __VA_ARGS__
+#else
+#define LAMINA_TRACE_ONLY(...)
+#endif
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -340,6 +364,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     __shared__ float s_wgt[kWaves * kMaxGroup];           // combine weights of the four triples
     __shared__ int s_wsum[kWaves];
 
+    LAMINA_TRACE_ONLY(
+        __shared__ unsigned long long s_stamp[kWaves][kTraceStamps];
+        const unsigned long long tr_enter = __builtin_amdgcn_s_memrealtime();
+        unsigned long long tr_range = 0, tr_issued = 0, tr_data = 0, tr_tiles_end = 0, tr_first_item = 0;
+        int tr_items = 0, tr_slots = 0, tr_iters = 0;)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -436,6 +465,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     } else {
         U = (long long)R * Hkv;
     }
+    LAMINA_TRACE_ONLY(tr_range = __builtin_amdgcn_s_memrealtime();)
     // Workers: the work-groups, or (fixed partitions, enough of them) the wavefronts on their own.
     const bool wave_items = wave_items_rule(mode, (unsigned)U, (unsigned)nwg);
     const int worker = wave_items ? j * kWaves + w : j;
@@ -450,6 +480,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             const i32x4 none = {-1, 0, 0, 0};             // no item here, so no row ends here
             *reinterpret_cast<i32x4 *>(prm.tails + 4 * j) = none;
         }
+        LAMINA_TRACE_ONLY(if (lane == 0 && j * kWaves + w < kTraceWaves)
+                              g_trace[(size_t)(j * kWaves + w) * kTraceWaveWords + 6] = 0;)
         return;
     }
 
@@ -1058,7 +1090,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         if (Q_AHEAD)
             request_q(nxt.r, nxt.g, qn);
         cn = score_scale(nxt.r, nxt.g);
+        LAMINA_TRACE_ONLY(tr_issued = __builtin_amdgcn_s_memrealtime();)
         wait_vmem_all();                                  // start-up only: nothing else to do yet
+        LAMINA_TRACE_ONLY(tr_data = __builtin_amdgcn_s_memrealtime();)
     }
     if (mode == kModeBalanced && tid == 0) {
         // Does a row that began in an earlier share end in this one?  Then this work-group's
@@ -1130,6 +1164,13 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
             fetch_pages(bt, rts, rlast, pg);
             int ts = cur.t0w;
             for (int k = 0; k < n_even; k += 2) {
+                LAMINA_TRACE_ONLY({
+                    // iterations 0..7 each, then every fourth
+                    const int at_ = tr_iters < 8 ? tr_iters : 8 + ((tr_iters - 8) >> 2);
+                    if ((tr_iters < 8 || ((tr_iters - 8) & 3) == 0) && at_ < kTraceStamps && lane == 0)
+                        s_stamp[w][at_] = __builtin_amdgcn_s_memrealtime();
+                    ++tr_iters;
+                })
                 consume(kA, vA, sc);
                 __builtin_amdgcn_sched_barrier(0);
                 target(k + 2, kb, vb, bt, rts, rlast);
@@ -1161,10 +1202,28 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                 __builtin_amdgcn_sched_barrier(0);
                 ts += 2 * step;
             }
+            LAMINA_TRACE_ONLY(++tr_items; tr_slots += n_even; tr_tiles_end = __builtin_amdgcn_s_memrealtime();)
         }
         finalize(id);
+        LAMINA_TRACE_ONLY(if (tr_first_item == 0) tr_first_item = __builtin_amdgcn_s_memrealtime();)
         ++slot;
     }
+    LAMINA_TRACE_ONLY(
+        if (lane == 0 && j * kWaves + w < kTraceWaves) {
+            unsigned long long *o = g_trace + (size_t)(j * kWaves + w) * kTraceWaveWords;
+            o[0] = tr_enter;
+            o[1] = tr_range;
+            o[2] = tr_issued;
+            o[3] = tr_data;
+            o[4] = tr_tiles_end;
+            o[6] = tr_items;
+            o[7] = tr_slots;
+            o[8] = tr_first_item;
+            o[9] = tr_iters;
+            for (int q = 0; q < kTraceStamps && (q < 8 ? q : 8 + (q - 8) * 4) < tr_iters; ++q)
+                o[16 + q] = s_stamp[w][q];
+            o[5] = __builtin_amdgcn_s_memrealtime();      // exit
+        })
 }
 
 // -------------------------------------------------------------------------------------------
@@ -1182,6 +1241,19 @@ constexpr int kMergeRowsPerBlock = 4;
 
 __global__ __launch_bounds__(64 * kMergeRowsPerBlock) void merge_partials_kernel(const MergeParams prm)
 {
+    LAMINA_TRACE_ONLY(
+        struct Stamp {
+            unsigned long long t0;
+            __device__ ~Stamp()
+            {
+                if ((threadIdx.x & 63) == 0 && blockIdx.x < kTraceMergeGroups) {
+                    unsigned long long *o = g_trace + (size_t)kTraceWaves * kTraceWaveWords +
+                                            (size_t)blockIdx.x * kTraceMergeWords;
+                    o[0] = t0;
+                    o[1] = __builtin_amdgcn_s_memrealtime();
+                }
+            }
+        } stamp{__builtin_amdgcn_s_memrealtime()};)
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * kMergeRowsPerBlock + (threadIdx.x >> 6);   // r * Hq + h
     if (row >= prm.rows)
@@ -1295,6 +1367,19 @@ __device__ __forceinline__ void store_merged_row(const BalancedMergeParams &prm,
 
 __global__ __launch_bounds__(256) void merge_balanced_kernel(const BalancedMergeParams prm)
 {
+    LAMINA_TRACE_ONLY(
+        struct Stamp {
+            unsigned long long t0;
+            __device__ ~Stamp()
+            {
+                if ((threadIdx.x & 63) == 0 && blockIdx.x < kTraceMergeGroups) {
+                    unsigned long long *o = g_trace + (size_t)kTraceWaves * kTraceWaveWords +
+                                            (size_t)blockIdx.x * kTraceMergeWords;
+                    o[0] = t0;
+                    o[1] = __builtin_amdgcn_s_memrealtime();
+                }
+            }
+        } stamp{__builtin_amdgcn_s_memrealtime()};)
     const int j = blockIdx.x + 1;                         // share 0 cannot hold the end of an earlier row
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
@@ -1449,15 +1534,12 @@ __device__ __forceinline__ float dequantise_e4m3fn(unsigned char b, float scale)
     return static_cast<float>(v[0]) * scale;
 }
 
-// One wavefront per (request, kv head): lane i moves elements 2i and 2i+1 of the K and V rows.
-__global__ __launch_bounds__(256) void append_kv_kernel(const NewTokenParams prm)
+// Write the new token's K and V rows of one (request, kv head) into the cache: lane i moves
+// elements 2i and 2i+1 (kk, vv: two bf16 each).  Skips positions outside the cache.
+__device__ __forceinline__ void append_row(const NewTokenParams &prm, int r, int g, int lane,
+                                           unsigned kk, unsigned vv)
 {
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);   // r * Hkv + g
-    if (row >= prm.rows)
-        return;
-    const int r = row / prm.Hkv;
-    const int g = row % prm.Hkv;
+    const int row = r * prm.Hkv + g;
     const int pos = prm.positions[r];
     if (pos < 0 || pos >= prm.pos_cap)
         return;
@@ -1473,8 +1555,6 @@ __global__ __launch_bounds__(256) void append_kv_kernel(const NewTokenParams prm
         off = (long long)r * prm.stride_req_b + (long long)g * prm.stride_head_b +
               (long long)pos * prm.stride_tok_b;
     }
-    const unsigned kk = reinterpret_cast<const unsigned *>(prm.k_new)[(size_t)row * 64 + lane];
-    const unsigned vv = reinterpret_cast<const unsigned *>(prm.v_new)[(size_t)row * 64 + lane];
     if (!prm.fp8) {
         reinterpret_cast<unsigned *>(prm.k_cache + off)[lane] = kk;
         reinterpret_cast<unsigned *>(prm.v_cache + off)[lane] = vv;
@@ -1492,6 +1572,18 @@ __global__ __launch_bounds__(256) void append_kv_kernel(const NewTokenParams prm
     }
 }
 
+// One wavefront per (request, kv head).
+__global__ __launch_bounds__(256) void append_kv_kernel(const NewTokenParams prm)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);   // r * Hkv + g
+    if (row >= prm.rows)
+        return;
+    const unsigned kk = reinterpret_cast<const unsigned *>(prm.k_new)[(size_t)row * 64 + lane];
+    const unsigned vv = reinterpret_cast<const unsigned *>(prm.v_new)[(size_t)row * 64 + lane];
+    append_row(prm, row / prm.Hkv, row % prm.Hkv, lane, kk, vv);
+}
+
 // One wavefront per (request, query head): the two-part case of the Sec. 4.2.2 identity with
 // I1 = previous tokens (given as A, ln S) and I2 = {new token} (A = v_new, ln S = s).
 __global__ __launch_bounds__(256) void fold_new_token_kernel(const NewTokenParams prm)
@@ -1506,6 +1598,10 @@ __global__ __launch_bounds__(256) void fold_new_token_kernel(const NewTokenParam
     const unsigned qq = reinterpret_cast<const unsigned *>(prm.q)[(size_t)row * 64 + lane];
     const unsigned kk = reinterpret_cast<const unsigned *>(prm.k_new)[kvrow * 64 + lane];
     const unsigned vv = reinterpret_cast<const unsigned *>(prm.v_new)[kvrow * 64 + lane];
+    // fold and append in one launch: the wavefront of a group's first head also moves the rows
+    // it has just read into the cache
+    if (prm.k_cache && (row % prm.Hq) % prm.G == 0)
+        append_row(prm, r, g, lane, kk, vv);
     float k0 = bf16_bits_to_float(kk & 0xFFFF), k1 = bf16_bits_to_float(kk >> 16);
     float v0 = bf16_bits_to_float(vv & 0xFFFF), v1 = bf16_bits_to_float(vv >> 16);
     if (prm.fp8) {
@@ -2170,6 +2266,54 @@ int lamina_fold_new_token(lamina_attn_t h, const void *q, const void *k_new, con
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail_hip(h, "fold kernel launch", e);
+    return LAMINA_OK;
+}
+
+int lamina_fold_new_token_and_append(lamina_attn_t h, const void *q, const void *k_new,
+                                     const void *v_new, const float *out_prev,
+                                     const float *lse_prev, void *out, float *lse, void *k_cache,
+                                     void *v_cache, const int32_t *positions,
+                                     const int32_t *block_table, const lamina_call_params *p)
+{
+    if (!h)
+        return LAMINA_ERR_INVALID_ARG;
+    h->err[0] = 0;
+    if (const char *msg = check_new_token_args(h, p, true, block_table))
+        return fail(h, LAMINA_ERR_INVALID_ARG, msg);
+    if (p->batch == 0)
+        return LAMINA_OK;
+    if (!q || !k_new || !v_new || !out_prev || !lse_prev || !out || !k_cache || !v_cache || !positions)
+        return fail(h, LAMINA_ERR_INVALID_ARG,
+                    "q, k_new, v_new, out_prev, lse_prev, out, k_cache, v_cache and positions must be "
+                    "non-NULL");
+    if (((uintptr_t)q | (uintptr_t)out_prev | (uintptr_t)out) % 8 != 0 ||
+        ((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)k_cache | (uintptr_t)v_cache) % 16 != 0)
+        return fail(h, LAMINA_ERR_INVALID_ARG,
+                    "k_new, v_new and the caches must be 16-byte aligned, the other tensors 8-byte");
+    if ((const void *)out_prev == (const void *)out && h->cfg.out_dtype != LAMINA_F32)
+        return fail(h, LAMINA_ERR_INVALID_ARG, "out may alias out_prev only for fp32 output");
+    NewTokenParams np;
+    fill_new_token_params(h, p, np);
+    np.q = static_cast<const unsigned short *>(q);
+    np.k_new = static_cast<const unsigned short *>(k_new);
+    np.v_new = static_cast<const unsigned short *>(v_new);
+    np.out_prev = out_prev;
+    np.lse_prev = lse_prev;
+    np.out = out;
+    np.lse = lse;
+    np.k_cache = static_cast<unsigned char *>(k_cache);
+    np.v_cache = static_cast<unsigned char *>(v_cache);
+    np.positions = positions;
+    np.block_table = block_table;
+    np.rows = p->batch * h->cfg.num_q_heads;
+    DeviceGuard guard(h->cfg.device);
+    if (!guard.ok())
+        return fail(h, LAMINA_ERR_HIP, "cannot select the handle's device");
+    hipLaunchKernelGGL(fold_new_token_kernel, dim3((unsigned)((np.rows + 3) / 4)), dim3(256), 0,
+                       static_cast<hipStream_t>(p->stream), np);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail_hip(h, "fold-and-append kernel launch", e);
     return LAMINA_OK;
 }
 

@@ -30,7 +30,8 @@ LAMINA_STATIC_SCRATCH_BYTES = 32 << 20
 EXPORTS = ("lamina_attn_create", "lamina_decode_attention", "lamina_attn_destroy",
            "lamina_attn_last_error", "lamina_attn_workspace_bytes", "lamina_attn_num_splits",
            "lamina_attn_split_tokens", "lamina_attn_count_partials", "lamina_append_kv",
-           "lamina_fold_new_token", "lamina_decode_attention_static",
+           "lamina_fold_new_token", "lamina_fold_new_token_and_append",
+           "lamina_decode_attention_static",
            "lamina_seqno_alloc", "lamina_seqno_free", "lamina_seqno_wait", "lamina_seqno_signal",
            "lamina_probe_stream_read")
 
@@ -60,16 +61,23 @@ class lamina_call_params(ctypes.Structure):
                 ("stream", ctypes.c_void_p)]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile the HIP library for gfx950 in-tree with hipcc; returns its path."""
+TRACE_LIB_PATH = os.path.join(_HERE, "liblamina_attn_trace.so")
+
+
+def build_library(verbose: bool = False, trace: bool = False) -> str:
+    """Compile the HIP library for gfx950 in-tree with hipcc; returns its path.  trace=True builds
+    the timeline variant (-DLAMINA_TRACE: the kernels stamp the device clock at a few points and
+    lamina_trace_read returns the stamps) next to the ordinary one; only `bench.py --timeline`
+    uses it."""
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", _INC, "-o", LIB_PATH, *_SRCS]
+    out = TRACE_LIB_PATH if trace else LIB_PATH
+    cmd = [hipcc, *HIPCC_FLAGS, *(["-DLAMINA_TRACE"] if trace else []), "-I", _INC, "-o", out, *_SRCS]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
     if verbose:
         print(" ".join(cmd))
-    return LIB_PATH
+    return out
 
 
 _lib = None
@@ -85,6 +93,30 @@ def library_is_stale() -> bool:
     return any(os.path.getmtime(d) > built for d in deps)
 
 
+def use_trace_library() -> None:
+    """Make this process load the timeline build instead of the ordinary library (must be called
+    before the first load()); builds it if it is missing or older than its sources."""
+    global LIB_PATH
+    if _lib is not None:
+        raise RuntimeError("the library is already loaded")
+    LIB_PATH = TRACE_LIB_PATH
+    if library_is_stale():
+        build_library(trace=True)
+
+
+def lamina_trace_read(words: int):
+    """Timeline build only: the device-side stamp array as a numpy uint64 vector."""
+    import numpy as np
+    lib = load()
+    buf = np.zeros(words, dtype=np.uint64)
+    lib.lamina_trace_read.restype = ctypes.c_int
+    lib.lamina_trace_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+    rc = lib.lamina_trace_read(buf.ctypes.data, words)
+    if rc != 0:
+        raise RuntimeError(f"lamina_trace_read: hip error {rc}")
+    return buf
+
+
 def load():
     """Load the built library, building it first if it is missing or older than any of its
     sources or headers (an edited kernel must never be tested through an old binary)."""
@@ -92,7 +124,7 @@ def load():
     if _lib is not None:
         return _lib
     if library_is_stale():
-        build_library()
+        build_library(trace=LIB_PATH == TRACE_LIB_PATH)
     lib = ctypes.CDLL(LIB_PATH)
     vp = ctypes.c_void_p
     lib.lamina_attn_create.restype = ctypes.c_int
@@ -126,6 +158,8 @@ def load():
     lib.lamina_fold_new_token.restype = ctypes.c_int
     lib.lamina_fold_new_token.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp,
                                           ctypes.POINTER(lamina_call_params)]
+    lib.lamina_fold_new_token_and_append.restype = ctypes.c_int
+    lib.lamina_fold_new_token_and_append.argtypes = [vp] * 12 + [ctypes.POINTER(lamina_call_params)]
     lib.lamina_decode_attention_static.restype = ctypes.c_int
     lib.lamina_decode_attention_static.argtypes = [ctypes.POINTER(lamina_attn_config), vp, vp, vp,
                                                    vp, vp, vp, vp,
@@ -177,6 +211,14 @@ def lamina_fold_new_token(h, q, k_new, v_new, out_prev, lse_prev, out, lse,
                           params: lamina_call_params) -> int:
     return load().lamina_fold_new_token(h, q, k_new, v_new, out_prev, lse_prev, out, lse,
                                         ctypes.byref(params) if params is not None else None)
+
+
+def lamina_fold_new_token_and_append(h, q, k_new, v_new, out_prev, lse_prev, out, lse, k_cache,
+                                     v_cache, positions, block_table,
+                                     params: lamina_call_params) -> int:
+    return load().lamina_fold_new_token_and_append(
+        h, q, k_new, v_new, out_prev, lse_prev, out, lse, k_cache, v_cache, positions,
+        block_table, ctypes.byref(params) if params is not None else None)
 
 
 def lamina_attn_destroy(h) -> int:
@@ -371,6 +413,27 @@ class DecodeAttention:
         rc = lamina_fold_new_token(self.handle, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
                                    out_prev.data_ptr(), lse_prev.data_ptr(), out.data_ptr(),
                                    lse.data_ptr(), p)
+        if rc != LAMINA_OK:
+            raise LaminaError(rc, lamina_attn_last_error(self.handle))
+        return out, lse
+
+    def fold_new_token_and_append(self, q, k_new, v_new, out_prev, lse_prev, k_cache, v_cache,
+                                  positions, block_table=None, out=None, lse=None, k_scale=None,
+                                  v_scale=None, stream=None):
+        """fold_new_token and append_kv in one launch."""
+        import torch
+        R, Hq, D = q.shape
+        if out is None:
+            out = torch.empty((R, Hq, D), device=q.device,
+                              dtype=torch.float32 if self.out_dtype == "f32" else torch.bfloat16)
+        if lse is None:
+            lse = torch.empty((R, Hq), device=q.device, dtype=torch.float32)
+        p = self.params_for(q, k_cache, block_table, k_scale, v_scale, stream)
+        rc = lamina_fold_new_token_and_append(
+            self.handle, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), out_prev.data_ptr(),
+            lse_prev.data_ptr(), out.data_ptr(), lse.data_ptr(), k_cache.data_ptr(),
+            v_cache.data_ptr(), positions.data_ptr(),
+            block_table.data_ptr() if block_table is not None else None, p)
         if rc != LAMINA_OK:
             raise LaminaError(rc, lamina_attn_last_error(self.handle))
         return out, lse

@@ -4,6 +4,7 @@ between the steps:
 
     wait(q arrived) -> attend over the previous tokens -> wait(k_n, v_n arrived)
                     -> fold the new token in -> append k_n, v_n to the cache
+                       (two launches, or the fused call that does both in one)
 
 A host thread stands in for the sender: it fills the pinned receive buffers and then advances
 the sequence numbers, q first and k_n, v_n later.  The result must equal the oracle over the
@@ -69,7 +70,7 @@ class LayerStep:
         self.sq_q, self.sq_kv = lamina.Seqno(), lamina.Seqno()
         self.rng = torch.Generator().manual_seed(seed)
 
-    def enqueue(self, s):
+    def enqueue(self, s, fused=False):
         t = self.t
         kw = dict(block_table=t.get("block_table"), k_scale=t.get("k_scale"),
                   v_scale=t.get("v_scale"))
@@ -80,6 +81,11 @@ class LayerStep:
         self.sq_kv.wait(1, timeout_us=20_000_000, stream=s)
         self.k_dev.copy_(self.k_host, non_blocking=True)
         self.v_dev.copy_(self.v_host, non_blocking=True)
+        if fused:                                         # one launch for fold + append
+            self.opb.fold_new_token_and_append(
+                self.q_dev, self.k_dev, self.v_dev, self.out_prev, self.lse_prev, t["k"], t["v"],
+                self.pos, out=self.out, lse=self.lse, stream=s, **kw)
+            return
         self.opb.fold_new_token(self.q_dev, self.k_dev, self.v_dev, self.out_prev, self.lse_prev,
                                 out=self.out, lse=self.lse, k_scale=t.get("k_scale"),
                                 v_scale=t.get("v_scale"), stream=s)
@@ -185,7 +191,7 @@ def test_layer_step_on_one_stream_eager_and_as_a_replayed_graph(name):
     ls.sq_kv.value = 1
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=s):
-        ls.enqueue(s)
+        ls.enqueue(s, fused=True)
     for it in range(3):
         q, kn, vn = ls.new_inputs()
         ls.reset()

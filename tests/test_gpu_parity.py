@@ -445,6 +445,11 @@ def test_append_then_two_phase_equals_one_phase(name):
     # phase 2: fold the new token in, without touching the cache
     out2, lse2 = op.fold_new_token(t["q"], k_new.to(d), v_new.to(d), out_prev, lse_prev,
                                    k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))
+    # the fused call (fold + append in one launch) on a copy of the cache: same bits as the two calls
+    k_copy, v_copy = t["k"].clone(), t["v"].clone()
+    out3, lse3 = op.fold_new_token_and_append(
+        t["q"], k_new.to(d), v_new.to(d), out_prev, lse_prev, k_copy, v_copy, positions.to(d),
+        block_table=t.get("block_table"), k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))
     # append, bit-exact against the host reference
     op.append_kv(k_new.to(d), v_new.to(d), t["k"], t["v"], positions.to(d),
                  block_table=t.get("block_table"), k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))
@@ -454,6 +459,9 @@ def test_append_then_two_phase_equals_one_phase(name):
     # compare only bytes that are defined (everything but poisoned padding is identical anyway)
     assert torch.equal(t["k"].cpu().view(iv), k_ref.view(iv))
     assert torch.equal(t["v"].cpu().view(iv), v_ref.view(iv))
+    assert torch.equal(k_copy.cpu().view(iv), k_ref.view(iv))
+    assert torch.equal(v_copy.cpu().view(iv), v_ref.view(iv))
+    assert torch.equal(out3, out2) and torch.equal(lse3, lse2)
     # one phase over the appended cache
     out1, lse1 = op(t["q"], t["k"], t["v"], t["seq_lens"], block_table=t.get("block_table"),
                     k_scale=t.get("k_scale"), v_scale=t.get("v_scale"))

@@ -1338,8 +1338,9 @@ __global__ __launch_bounds__(64 * kMergeRowsPerBlock) void merge_partials_kernel
 // that case needs are requested together with the record, before it is known whether they
 // will be used: the common case costs one memory round trip, not three (record, weights,
 // outputs one after the other), and this launch is pure latency on the call's critical path.
-// Wavefront w combines heads w, w + 4, ...; within a wavefront the two half-waves each hold
-// one piece, every lane four output columns.
+// One wavefront per head of the group (the work-group has G of them), so no wavefront works
+// through heads one after the other; within a wavefront the two half-waves each hold one
+// piece, every lane four output columns.
 // -------------------------------------------------------------------------------------------
 struct BalancedMergeParams {
     const float *part_out;             // [slot][G][128]
@@ -1365,7 +1366,7 @@ __device__ __forceinline__ void store_merged_row(const BalancedMergeParams &prm,
     }
 }
 
-__global__ __launch_bounds__(256) void merge_balanced_kernel(const BalancedMergeParams prm)
+__global__ __launch_bounds__(64 * kMaxGroup) void merge_balanced_kernel(const BalancedMergeParams prm)
 {
     LAMINA_TRACE_ONLY(
         struct Stamp {
@@ -1382,109 +1383,93 @@ __global__ __launch_bounds__(256) void merge_balanced_kernel(const BalancedMerge
         } stamp{__builtin_amdgcn_s_memrealtime()};)
     const int j = blockIdx.x + 1;                         // share 0 cannot hold the end of an earlier row
     const int lane = threadIdx.x & 63;
-    const int wv = threadIdx.x >> 6;
+    const int hl = threadIdx.x >> 6;                      // one wavefront per head of the group
     const int half = lane >> 5;
     const int c4 = (lane & 31) * 4;
     const int G = prm.G;
-    constexpr int kHeadsPerWave = kMaxGroup / 4;
     const i32x4 rec = *reinterpret_cast<const i32x4 *>(prm.tails + 4 * j);
     // the two-piece case, requested before the record is known: the tail piece (slot 2j) in
     // the lower half-wave, the head piece of the share before (slot 2j - 1) in the upper one
     const size_t slot2 = (size_t)(2 * j - half);
-    f32x4 t2[kHeadsPerWave];
-    float l2[kHeadsPerWave];
-#pragma unroll
-    for (int i = 0; i < kHeadsPerWave; ++i) {
-        const int hl = min(wv + 4 * i, G - 1);
-        t2[i] = *reinterpret_cast<const f32x4 *>(prm.part_out + (slot2 * G + hl) * kHeadDim + c4);
-        l2[i] = prm.part_lse[slot2 * G + hl];
-    }
+    const f32x4 t2 = *reinterpret_cast<const f32x4 *>(prm.part_out + (slot2 * G + hl) * kHeadDim + c4);
+    const float l2 = prm.part_lse[slot2 * G + hl];
     if (rec[0] < 0)
         return;                                           // no row ends in this share
     const int r = rec[1], g = rec[2], a = rec[3];
+    const size_t row = (size_t)r * prm.Hq + g * G + hl;
     if (a == j - 1) {
-#pragma unroll
-        for (int i = 0; i < kHeadsPerWave; ++i) {
-            const int hl = wv + 4 * i;
-            if (hl >= G)
-                break;
-            const float lo = __shfl_xor(l2[i], 32);
-            const float M = fmaxf(l2[i], lo);
-            const float w = __expf(l2[i] - M);
-            const float W = w + __expf(lo - M);
-            f32x4 o = w * t2[i];
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                o[c] += __shfl_xor(o[c], 32);
-            const size_t row = (size_t)r * prm.Hq + g * G + hl;
-            if (half == 0)
-                store_merged_row(prm, row, c4, o * (1.0f / W));
-            if (lane == 0 && prm.lse)
-                prm.lse[row] = M + logf(W);
-        }
-        return;
-    }
-    // a row spread over three or more shares: piece p of it (p = 0 .. np - 1) lies in slot
-    // 2a + 1 for p = 0 and in slot 2 (a + p) otherwise.  The weights (lane p holds piece p's)
-    // and the first sixteen pieces' outputs are requested together, one round trip.
-    const int np = j - a + 1;
-    auto slot_of = [&](int p) { return (size_t)(p == 0 ? 2 * a + 1 : 2 * (a + p)); };
-    for (int hl = wv; hl < G; hl += 4) {
-        const float *pl = prm.part_lse + hl;
-        const float *po = prm.part_out + (size_t)hl * kHeadDim + c4;
-        float W = 0.0f, M = -INFINITY;
-        f32x4 o = {0.f, 0.f, 0.f, 0.f};
-        for (int p0 = 0; p0 < np; p0 += 64) {
-            const int cnt = min(64, np - p0);
-            const float l = (lane < cnt) ? pl[slot_of(p0 + lane) * G] : -INFINITY;
-            f32x4 t[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k)                   // pieces beyond cnt re-read the last one
-                t[k] = *reinterpret_cast<const f32x4 *>(
-                    po + slot_of(p0 + min(2 * k + half, cnt - 1)) * G * kHeadDim);
-            float Mc = l;
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1)
-                Mc = fmaxf(Mc, __shfl_xor(Mc, off));
-            const float Mn = fmaxf(M, Mc);                // running maximum over chunks of 64 pieces
-            const float rescale = __expf(M - Mn);         // 0 for the first chunk
-            M = Mn;
-            const float e = (lane < cnt) ? __expf(l - M) : 0.0f;
-            W = W * rescale + e;
-            o *= rescale;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int p = 2 * k + half;
-                const float wgt = __shfl(e, min(p, cnt - 1));
-                o += ((p < cnt) ? wgt : 0.0f) * t[k];
-            }
-            for (int i0 = 8; i0 < (cnt + 1) / 2; i0 += 8) {
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const int p = 2 * (i0 + k) + half;
-                    t[k] = *reinterpret_cast<const f32x4 *>(
-                        po + slot_of(p0 + min(p, cnt - 1)) * G * kHeadDim);
-                }
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const int p = 2 * (i0 + k) + half;
-                    const float wgt = __shfl(e, min(p, cnt - 1));
-                    o += ((p < cnt) ? wgt : 0.0f) * t[k];
-                }
-            }
-        }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1)
-            W += __shfl_xor(W, off);
+        const float lo = __shfl_xor(l2, 32);
+        const float M = fmaxf(l2, lo);
+        const float w = __expf(l2 - M);
+        const float W = w + __expf(lo - M);
+        f32x4 o = w * t2;
 #pragma unroll
         for (int c = 0; c < 4; ++c)
             o[c] += __shfl_xor(o[c], 32);
-        const size_t row = (size_t)r * prm.Hq + g * G + hl;
         if (half == 0)
             store_merged_row(prm, row, c4, o * (1.0f / W));
         if (lane == 0 && prm.lse)
             prm.lse[row] = M + logf(W);
+        return;
     }
+    // a row spread over three or more shares: piece p of it (p = 0 .. np - 1) lies in slot
+    // 2a + 1 for p = 0 and in slot 2 (a + p) otherwise.  The weights (lane p holds piece p's)
+    // and the first sixteen pieces' outputs are requested together: one more round trip.
+    const int np = j - a + 1;
+    auto slot_of = [&](int p) { return (size_t)(p == 0 ? 2 * a + 1 : 2 * (a + p)); };
+    const float *pl = prm.part_lse + hl;
+    const float *po = prm.part_out + (size_t)hl * kHeadDim + c4;
+    float W = 0.0f, M = -INFINITY;
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+    for (int p0 = 0; p0 < np; p0 += 64) {
+        const int cnt = min(64, np - p0);
+        const float l = (lane < cnt) ? pl[slot_of(p0 + lane) * G] : -INFINITY;
+        f32x4 t[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)                       // pieces beyond cnt re-read the last one
+            t[k] = *reinterpret_cast<const f32x4 *>(
+                po + slot_of(p0 + min(2 * k + half, cnt - 1)) * G * kHeadDim);
+        float Mc = l;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1)
+            Mc = fmaxf(Mc, __shfl_xor(Mc, off));
+        const float Mn = fmaxf(M, Mc);                    // running maximum over chunks of 64 pieces
+        const float rescale = __expf(M - Mn);             // 0 for the first chunk
+        M = Mn;
+        const float e = (lane < cnt) ? __expf(l - M) : 0.0f;
+        W = W * rescale + e;
+        o *= rescale;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int p = 2 * k + half;
+            const float wgt = __shfl(e, min(p, cnt - 1));
+            o += ((p < cnt) ? wgt : 0.0f) * t[k];
+        }
+        for (int i0 = 8; i0 < (cnt + 1) / 2; i0 += 8) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int p = 2 * (i0 + k) + half;
+                t[k] = *reinterpret_cast<const f32x4 *>(
+                    po + slot_of(p0 + min(p, cnt - 1)) * G * kHeadDim);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int p = 2 * (i0 + k) + half;
+                const float wgt = __shfl(e, min(p, cnt - 1));
+                o += ((p < cnt) ? wgt : 0.0f) * t[k];
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        W += __shfl_xor(W, off);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        o[c] += __shfl_xor(o[c], 32);
+    if (half == 0)
+        store_merged_row(prm, row, c4, o * (1.0f / W));
+    if (lane == 0 && prm.lse)
+        prm.lse[row] = M + logf(W);
 }
 
 // -------------------------------------------------------------------------------------------
@@ -2109,7 +2094,8 @@ int enqueue_decode(lamina_attn *h, const void *q, const void *k_cache, const voi
             bp.Hq = c.num_q_heads;
             bp.G = h->group;
             bp.out_is_bf16 = mp.out_is_bf16;
-            hipLaunchKernelGGL(merge_balanced_kernel, dim3((unsigned)(wgs - 1)), dim3(256), 0, stream, bp);
+            hipLaunchKernelGGL(merge_balanced_kernel, dim3((unsigned)(wgs - 1)),
+                               dim3((unsigned)(64 * h->group)), 0, stream, bp);
             e = hipGetLastError();
             if (e != hipSuccess)
                 return fail_hip(h, "merge kernel launch", e);

@@ -123,7 +123,9 @@ def timeline(args, w, lens, op, step, torch, lamina, W, out_dtype) -> int:
     print("  wavefront enters the kernel               ", pct(us(main[:, 0][main[:, 0] > 0])))
     print("  its range of work is known                ", pct(us(m[:, 1])))
     print("  its first 32 KiB of loads are issued      ", pct(us(m[:, 2])))
-    print("  ... and have arrived                      ", pct(us(m[:, 3])))
+    got = m[:, 3] > 0
+    if got.any():
+        print("  ... and have been consumed                ", pct(us(m[got, 3])))
     print("  its first item is finished                ", pct(us(m[:, 8])))
     print("  its last tile is finished                 ", pct(us(m[:, 4])))
     print("  wavefront exits                           ", pct(us(m[:, 5])))

@@ -1072,9 +1072,13 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
     find_next(nxt);
     int pvA = 0, pvB = 0;           // pages of the next refill of set A / set B (paged caches)
     if (nxt.slot >= 0) {
-        // prologue: the first two tile slots of this wavefront's first item, and its Q; the
+        // prologue: the Q rows of this wavefront's first item and its first two tile slots; the
         // pages of slots 2 and 3 as if they lay in the same item (put right at the item's
-        // start if they do not)
+        // start if they do not).  Q goes first: loads return in order, so the first item can
+        // start on its first tile as soon as that has arrived, without waiting for the second
+        // (a call of 20 requests x 1024 tokens, all start-up: 20.0 -> 18.6 us).
+        if (Q_AHEAD)
+            request_q(nxt.r, nxt.g, qn);
         const int pv0 = load_pages(nxt.bt, nxt.t0w, nxt.t1 - 1);
         const int pv1 = load_pages(nxt.bt, nxt.t0w + step, nxt.t1 - 1);
         pvA = load_pages(nxt.bt, nxt.t0w + 2 * step, nxt.t1 - 1);
@@ -1087,12 +1091,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
         fetch_pages(nxt.bt, nxt.t0w + step, nxt.t1 - 1, pg);
         issue_loads(nxt.kbase, nxt.vbase, nxt.t0w + step, nxt.t1 - 1, pg, kB, vB);
         __builtin_amdgcn_sched_barrier(0);
-        if (Q_AHEAD)
-            request_q(nxt.r, nxt.g, qn);
         cn = score_scale(nxt.r, nxt.g);
         LAMINA_TRACE_ONLY(tr_issued = __builtin_amdgcn_s_memrealtime();)
-        wait_vmem_all();                                  // start-up only: nothing else to do yet
-        LAMINA_TRACE_ONLY(tr_data = __builtin_amdgcn_s_memrealtime();)
     }
     if (mode == kModeBalanced && tid == 0) {
         // Does a row that began in an earlier share end in this one?  Then this work-group's
@@ -1169,6 +1169,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const MainPara
                     const int at_ = tr_iters < 8 ? tr_iters : 8 + ((tr_iters - 8) >> 2);
                     if ((tr_iters < 8 || ((tr_iters - 8) & 3) == 0) && at_ < kTraceStamps && lane == 0)
                         s_stamp[w][at_] = __builtin_amdgcn_s_memrealtime();
+                    if (tr_iters == 1)
+                        tr_data = s_stamp[w][1];          // first pair of tiles consumed
                     ++tr_iters;
                 })
                 consume(kA, vA, sc);

@@ -295,10 +295,12 @@ __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0
 //   rows mode       n = 1 (the row is never cut),
 //   fixed mode      n = number of `unit`-token partitions of seq_lens[r] (at least one),
 //   balanced mode   n = number of 128-token (bf16) / 256-token (fp8) blocks (at least one).
-// Work-group j takes a contiguous range of units, all ranges equal to within one unit.  In
+// Work-group j takes a contiguous range of units: all ranges equal to within one unit, except
+// that large balanced calls weight the ranges by the parity of j (share_skew: work-groups go
+// round-robin to the eight dies, and the odd dies stream several per cent slower).  In
 // rows and fixed mode every unit is one ITEM; in balanced mode an item is the part of one row
-// that falls into the work-group's range, however long -- so every work-group streams the same
-// number of tokens whatever the mix of lengths, and a row is cut only where a range ends
+// that falls into the work-group's range, however long -- so every work-group streams its
+// share of the tokens whatever the mix of lengths, and a row is cut only where a range ends
 // (at most one extra partial result per work-group).  Every work-group derives its range
 // itself from seq_lens (a prefix sum in LDS), so the host never reads seq_lens and no
 // planning kernel runs.
@@ -308,8 +310,10 @@ __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0
 // (max, denominator, output) triples through LDS -- the same identity as the cross-partition
 // merge.  An item that covers its whole row is written straight to out/lse; otherwise the
 // item writes the partial pair (A_q(I), ln S_q(I)) of Sec. 4.2.2 to the workspace, at piece
-// index `unit number` (fixed mode) or `row number + work-group number` (balanced mode; both
-// grow along the stream and one of them changes between consecutive items).
+// index `unit number` (fixed mode), or in balanced mode at one of the work-group's own two
+// slots: 2j for the piece that continues a row begun by an earlier work-group, 2j+1 for the
+// piece that begins a row which a later work-group continues.  A 16-byte record per
+// work-group says where its range starts, so the merge finds a row's pieces without a search.
 //
 // Streaming.  Each wavefront keeps two register sets of 16 KiB of K+V in flight and refills a
 // set as soon as its registers have been read.  When an item runs out of tiles the refills

@@ -88,7 +88,8 @@ def library_is_stale() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
     built = os.path.getmtime(LIB_PATH)
-    deps = list(_SRCS) + [os.path.join(_INC, f) for f in sorted(os.listdir(_INC))
+    csrc = os.path.join(_HERE, "csrc")
+    deps = list(_SRCS) + [os.path.join(d, f) for d in (_INC, csrc) for f in sorted(os.listdir(d))
                           if f.endswith(".h")]
     return any(os.path.getmtime(d) > built for d in deps)
 

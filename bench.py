@@ -92,6 +92,59 @@ def read_probe(args, torch, lamina, dev) -> int:
     return 0
 
 
+def valu_probe(args, w, torch, lamina, W, dev) -> int:
+    """The operator on the matrix cores (the product's call, rows never cut, fp32 output) against
+    the same operator on the vector ALU only (lamina_probe_valu_attention), same inputs, same
+    streaming: what the matrix cores buy.  One JSON line."""
+    import numpy as np
+    if w.kv_dtype != "bf16" or w.block_size != 0:
+        print("bench.py --valu-probe: needs a bf16 contiguous workload", file=sys.stderr)
+        return 2
+    b = W.generate(w, threads=16)
+    lens = b["seq_lens"].numpy()
+    cap = int(lens.max())
+    op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=w.batch, max_seq_len=cap,
+                                kv_dtype="bf16", out_dtype="f32", block_size=0, num_splits=1)
+    t = {k: v.to(dev) for k, v in b.items() if isinstance(v, torch.Tensor)}
+    copies = max(1, args.copies)
+    ks = [t["k"]] + [t["k"].clone() for _ in range(copies - 1)]
+    vs = [t["v"]] + [t["v"].clone() for _ in range(copies - 1)]
+    outs = {n: (torch.empty((w.batch, w.num_q_heads, 128), device=dev),
+                torch.empty((w.batch, w.num_q_heads), device=dev)) for n in ("mfma", "valu")}
+
+    def mfma(i):
+        op(t["q"], ks[i % copies], vs[i % copies], t["seq_lens"], out=outs["mfma"][0],
+           lse=outs["mfma"][1])
+
+    def valu(i):
+        lamina.valu_attention(t["q"], ks[i % copies], vs[i % copies], t["seq_lens"],
+                              w.num_kv_heads, cap, out=outs["valu"][0], lse=outs["valu"][1])
+
+    ab = W.algorithmic_bytes(w, lens, out_bytes=4, partial_results=0)
+    need = ab["total"] - ab["partials"]
+    res = {"valu_probe_workload": w.name, "heads": f"{w.num_q_heads}/{w.num_kv_heads}",
+           "requests": w.batch, "needed_bytes": int(need), "steps": args.steps}
+    for name, fn in (("mfma", mfma), ("valu", valu), ("mfma_again", mfma)):
+        for i in range(args.warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            fn(i)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / args.steps
+        res[name] = {"us_per_call": round(us, 2), "gbps": round(need / us / 1e3, 1),
+                     "pct_of_hbm_peak": round(need / us / 1e3 / 8000 * 100, 2)}
+    d = (outs["mfma"][0] - outs["valu"][0]).abs().max().item()
+    fin = torch.isfinite(outs["mfma"][1])
+    dl = (outs["mfma"][1][fin] - outs["valu"][1][fin]).abs().max().item() if fin.any() else 0.0
+    res["max_abs_difference_out"] = d
+    res["max_abs_difference_lse"] = dl
+    op.close()
+    print(json.dumps(res))
+    return 0 if d <= 2e-3 and dl <= 1e-3 else 1
+
+
 def timeline(args, w, lens, op, step, torch, lamina, W, out_dtype) -> int:
     """Time-resolved account of one call from the timeline build.  Times are microseconds on the
     device's constant 100 MHz clock, counted from the entry of the call's first wavefront;
@@ -302,6 +355,10 @@ def main() -> int:
                          "(same persistent grid and load shape as the main pass) over buffers of "
                          "--probe-mib MiB: what the memory system delivers to a pure reader")
     ap.add_argument("--probe-mib", type=int, default=1024)
+    ap.add_argument("--valu-probe", action="store_true",
+                    help="instead of the benchmark line, time the product's call (matrix cores) "
+                         "against the library's vector-ALU-only version of the same operator "
+                         "on the same bf16 contiguous inputs, rows never cut")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the operator, run a plain device copy of 1 GiB a few times "
                          "(reference reading for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -347,6 +404,8 @@ def main() -> int:
             kv_dtype=args.kv_dtype or w.kv_dtype, batch=args.batch or w.batch,
             num_q_heads=hq, num_kv_heads=hkv,
             len_recipe=("fixed", args.fixed_len) if args.fixed_len else w.len_recipe)
+    if args.valu_probe:
+        return valu_probe(args, w, torch, lamina, W, dev)
     t_gen = time.time()
     b = W.generate(w, threads=16)
     lens = b["seq_lens"].numpy()

@@ -33,7 +33,7 @@ EXPORTS = ("lamina_attn_create", "lamina_decode_attention", "lamina_attn_destroy
            "lamina_fold_new_token", "lamina_fold_new_token_and_append",
            "lamina_decode_attention_static",
            "lamina_seqno_alloc", "lamina_seqno_free", "lamina_seqno_wait", "lamina_seqno_signal",
-           "lamina_probe_stream_read")
+           "lamina_probe_stream_read", "lamina_probe_valu_attention")
 
 LAMINA_SEQNO_REACHED = 0
 LAMINA_SEQNO_TIMED_OUT = 1
@@ -167,6 +167,9 @@ def load():
                                                    ctypes.POINTER(lamina_call_params)]
     lib.lamina_probe_stream_read.restype = ctypes.c_int
     lib.lamina_probe_stream_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp, vp]
+    lib.lamina_probe_valu_attention.restype = ctypes.c_int
+    lib.lamina_probe_valu_attention.argtypes = [vp] * 6 + [ctypes.c_int] * 4 + [ctypes.c_int64] * 3 + [
+        ctypes.c_float, ctypes.c_int, vp]
     _lib = lib
     return lib
 
@@ -261,6 +264,41 @@ def lamina_probe_stream_read(buf, nbytes: int, nontemporal: bool, work_groups: i
     """Read-only streaming pass over nbytes of device memory at address buf (integers)."""
     return load().lamina_probe_stream_read(buf, nbytes, 1 if nontemporal else 0, work_groups,
                                            sink, stream)
+
+
+def lamina_probe_valu_attention(q, k_cache, v_cache, seq_lens, out, lse, batch: int,
+                                num_q_heads: int, num_kv_heads: int, max_seq_len: int,
+                                kv_stride_req: int, kv_stride_head: int, kv_stride_tok: int,
+                                softmax_scale: float, work_groups: int, stream) -> int:
+    """The operator on the vector ALU only (measurement aid); pointers are integers."""
+    return load().lamina_probe_valu_attention(q, k_cache, v_cache, seq_lens, out, lse, batch,
+                                              num_q_heads, num_kv_heads, max_seq_len,
+                                              kv_stride_req, kv_stride_head, kv_stride_tok,
+                                              softmax_scale, work_groups, stream)
+
+
+def valu_attention(q, k_cache, v_cache, seq_lens, num_kv_heads: int, max_seq_len: int,
+                   out=None, lse=None, stream=None, work_groups: int = 0):
+    """Tensor-level wrapper of lamina_probe_valu_attention for bf16 contiguous caches
+    [R][Hkv][L][128] (any strides that are multiples of 8 elements); returns (out, lse)."""
+    import torch
+    R, Hq, D = q.shape
+    assert D == 128 and q.dtype == torch.bfloat16 and q.is_contiguous()
+    assert k_cache.dtype == torch.bfloat16 and k_cache.stride() == v_cache.stride()
+    assert k_cache.stride(3) == 1 and seq_lens.dtype == torch.int32
+    if out is None:
+        out = torch.empty((R, Hq, D), device=q.device, dtype=torch.float32)
+    if lse is None:
+        lse = torch.empty((R, Hq), device=q.device, dtype=torch.float32)
+    st = stream if stream is not None else torch.cuda.current_stream(q.device)
+    rc = lamina_probe_valu_attention(q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(),
+                                     seq_lens.data_ptr(), out.data_ptr(), lse.data_ptr(), R, Hq,
+                                     num_kv_heads, max_seq_len, k_cache.stride(0),
+                                     k_cache.stride(1), k_cache.stride(2), 0.0, work_groups,
+                                     st.cuda_stream)
+    if rc != LAMINA_OK:
+        raise LaminaError(rc, "lamina_probe_valu_attention")
+    return out, lse
 
 
 class Seqno:

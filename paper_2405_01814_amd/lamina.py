@@ -62,16 +62,24 @@ class lamina_call_params(ctypes.Structure):
 
 
 TRACE_LIB_PATH = os.path.join(_HERE, "liblamina_attn_trace.so")
+HOSTSAN_LIB_PATH = os.path.join(_HERE, "liblamina_attn_hostsan.so")
+HOSTSAN_ENV = "LAMINA_HOST_SANITIZE"
+# AddressSanitizer + UBSan on the HOST half of the library only (argument checks, planning,
+# launch set-up); the device code is compiled as always.
+HOSTSAN_FLAGS = ["-Xarch_host", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host",
+                 "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=all"]
 
 
-def build_library(verbose: bool = False, trace: bool = False) -> str:
+def build_library(verbose: bool = False, trace: bool = False, host_sanitize: bool = False) -> str:
     """Compile the HIP library for gfx950 in-tree with hipcc; returns its path.  trace=True builds
     the timeline variant (-DLAMINA_TRACE: the kernels stamp the device clock at a few points and
     lamina_trace_read returns the stamps) next to the ordinary one; only `bench.py --timeline`
-    uses it."""
+    uses it.  host_sanitize=True builds a variant whose host code runs under ASan + UBSan (its
+    process must preload the sanitizer runtime, see host_sanitizer_env); only tests use it."""
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
-    out = TRACE_LIB_PATH if trace else LIB_PATH
-    cmd = [hipcc, *HIPCC_FLAGS, *(["-DLAMINA_TRACE"] if trace else []), "-I", _INC, "-o", out, *_SRCS]
+    out = HOSTSAN_LIB_PATH if host_sanitize else (TRACE_LIB_PATH if trace else LIB_PATH)
+    cmd = [hipcc, *HIPCC_FLAGS, *(HOSTSAN_FLAGS if host_sanitize else []),
+           *(["-DLAMINA_TRACE"] if trace else []), "-I", _INC, "-o", out, *_SRCS]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
@@ -92,6 +100,29 @@ def library_is_stale() -> bool:
     deps = list(_SRCS) + [os.path.join(d, f) for d in (_INC, csrc) for f in sorted(os.listdir(d))
                           if f.endswith(".h")]
     return any(os.path.getmtime(d) > built for d in deps)
+
+
+def host_sanitized() -> bool:
+    """True if this process is to run the host-sanitized build of the library."""
+    return os.environ.get(HOSTSAN_ENV, "") == "1"
+
+
+def host_sanitizer_env() -> dict:
+    """Environment for a child process that loads the host-sanitized library: the compiler's ASan
+    runtime (which also carries the UBSan handlers) has to be in the process first, so it is
+    preloaded ahead of whatever is preloaded already; leak checking is off because neither the
+    interpreter nor the GPU runtime free everything at exit."""
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    rt = subprocess.run([hipcc, "-print-file-name=libclang_rt.asan-x86_64.so"], check=True,
+                        capture_output=True, text=True).stdout.strip()
+    if not os.path.isabs(rt) or not os.path.exists(rt):
+        raise RuntimeError("the compiler's AddressSanitizer runtime was not found: " + rt)
+    env = dict(os.environ)
+    env["LD_PRELOAD"] = rt + (":" + env["LD_PRELOAD"] if env.get("LD_PRELOAD") else "")
+    env["ASAN_OPTIONS"] = "detect_leaks=0:abort_on_error=1:protect_shadow_gap=0"
+    env["UBSAN_OPTIONS"] = "print_stacktrace=1:halt_on_error=1"
+    env[HOSTSAN_ENV] = "1"
+    return env
 
 
 def use_trace_library() -> None:
@@ -121,11 +152,13 @@ def lamina_trace_read(words: int):
 def load():
     """Load the built library, building it first if it is missing or older than any of its
     sources or headers (an edited kernel must never be tested through an old binary)."""
-    global _lib
+    global _lib, LIB_PATH
     if _lib is not None:
         return _lib
+    if host_sanitized() and LIB_PATH != HOSTSAN_LIB_PATH:
+        LIB_PATH = HOSTSAN_LIB_PATH
     if library_is_stale():
-        build_library(trace=LIB_PATH == TRACE_LIB_PATH)
+        build_library(trace=LIB_PATH == TRACE_LIB_PATH, host_sanitize=LIB_PATH == HOSTSAN_LIB_PATH)
     lib = ctypes.CDLL(LIB_PATH)
     vp = ctypes.c_void_p
     lib.lamina_attn_create.restype = ctypes.c_int

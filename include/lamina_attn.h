@@ -60,10 +60,11 @@ typedef struct {
                                1: never; N>1: into N partitions of ceil(max_seq_len / N) tokens
                                (rounded up to a multiple of 256), each processed on its own;
                                0: the library decides, normally "balanced": per call, from seq_lens,
-                               every work-group gets a fixed share of the call's work (tokens in
-                               blocks of 128, or 256 for fp8, plus one block per row for its fixed
-                               cost; shares are equal, except that from 12 blocks per work-group
-                               on the even-numbered work-groups take 1/32, from 24 blocks on 1/16
+                               every work-group (one per compute unit) gets a fixed share of the
+                               call's work (tokens in blocks of 128, or 256 for fp8, plus one
+                               block per row for its fixed cost; shares are equal, except that
+                               from 12 blocks per work-group
+                               on the even-numbered work-groups take 1/32, from 48 blocks on 1/16
                                more and the odd-numbered ones as much less: they run on dies of
                                different speed) and a row is cut only where one share ends and
                                the next begins                                                   */

@@ -233,7 +233,8 @@ __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0
 
 // -------------------------------------------------------------------------------------------
 // Main pass: a persistent kernel.  The grid is a fixed number of work-groups (two per compute
-// unit) that stay resident and share out the call's work among themselves.
+// unit; one for balanced shares) that stay resident and share out the call's work among
+// themselves.
 //
 // Work.  The rows (request r, kv head g), g fastest, are laid end to end as a stream of UNITS:
 // row (r, g) holds n(r) units, where
@@ -1588,7 +1589,7 @@ struct lamina_attn {
     float scale;
     float *workspace;            // part_out, part_lse, unit prefix sums; nullptr in rows mode
     size_t workspace_bytes;
-    int resident_wgs;            // persistent grid: two work-groups per compute unit
+    int resident_wgs;            // two work-groups per compute unit (see grid_for)
     char err[256];
 };
 
@@ -1753,13 +1754,21 @@ class DeviceGuard {
 };
 
 // Work-groups of the main pass for a call with `batch` requests: never more than can be
-// resident, never more than there can be units.
+// resident, never more than there can be units.  Balanced shares run ONE work-group per
+// compute unit: four wavefronts with two tiles in flight each already draw a compute unit's
+// share of the memory system (every workload streams as fast with 256 work-groups as with 512),
+// and half as many shares are half as many cut rows, partial results and merge work-groups.
+// Same box, 512 -> 256 work-groups: workload 3 83.4 -> 82.7 us, workload 7 373.5 -> 369.7 us,
+// 16 x 8 x 131072 tokens 1208 -> 1199 us, 20 requests x 4096 tokens 62.7 -> 61.3 us, 4 x 32768
+// 89.9 -> 87.0 us, 1 x 8192 19.9 -> 17.4 us.  Whole rows and caller-fixed partitions keep two
+// per compute unit (512 rows of workload 2 are one row each; 0.2-0.9 % slower with one).
 int grid_for(const lamina_attn *h, int batch)
 {
     const Plan pl = {h->mode, h->parts, h->unit};
     long long wgs = (long long)batch * h->cfg.num_kv_heads * max_units_per_row(h->cfg, pl);
-    if (wgs > h->resident_wgs)
-        wgs = h->resident_wgs;
+    const long long cap = h->mode == kModeBalanced ? (h->resident_wgs + 1) / 2 : h->resident_wgs;
+    if (wgs > cap)
+        wgs = cap;
     return (int)wgs;
 }
 

@@ -16,24 +16,26 @@
 // eight accelerator dies, and on every chip measured the odd dies stream 7-14 % slower than the
 // even ones; with equal shares the even dies run dry while the odd ones still have a twelfth of
 // their work, and the call's last tenth runs at half the memory rate.  Measured with the skew
-// swept 0 / 2 / 4 / 6 on one chip: workload 5 takes 374 / 367 / 362 / 367 us, workload 7
-// 378 / 374 / 371 / 376 us, workload 3 85.2 / 84.4 / 84.3 / 84.8 us.  With a skew, worker j
-// starts at unit floor(U * c(j) / c(n)), c(j) = 64 j + skew * (j odd).
+// swept 0 / 2 / 4 / 6 on one chip (512 work-groups): workload 5 takes 374 / 367 / 362 / 367 us,
+// workload 7 378 / 374 / 371 / 376 us, workload 3 85.2 / 84.4 / 84.3 / 84.8 us.  With a skew,
+// worker j starts at unit floor(U * c(j) / c(n)), c(j) = 64 j + skew * (j odd).
 // The main pass and the host-side accounting both use these two functions.
 // (U never exceeds 2^30 -- checked at creation -- and c(n) < 2^17, so 64-bit products are exact.)
 constexpr int kParitySkew = 4;
-// The skew pays once a share is long enough for the dies' different speeds to show: a call
-// with ten units (0.6 MB) per work-group is still filling the memory pipeline for a third of
-// its time, every work-group's time is then proportional to its own share, and a skew only
-// makes the even ones last longer (20 requests x 8 kv heads x 4096 tokens: 62.5 us without,
-// 63.5 us with).  Full skew from 24 units per work-group, half of it from 12.  (Below two
-// units per work-group it has to be zero in any case: the merge pass relies on every
-// work-group between a row's first and last piece holding a piece of it.)
+// The skew pays once a share is long enough for the dies' different speeds to show; a short
+// call is still filling the memory pipeline for a good part of its time, which the dies do
+// alike.  Measured with 256 work-groups, units per work-group / skew 0, 2, 4: 16 (8 requests x
+// 8 kv heads x 8192 tokens) 52.1 / 49.6 / - us; 21 (20 x 8 x 4096) 61.7 / 61.3 / - us; 28
+// (workload 3) - / 82.7 / 83.1 us; 32 (4 x 8 x 32768) - / 87.7 / 87.0 us; 41 (20 x 8 x 8192)
+// - / 109.1 / 110.5 us; beyond that the full skew.  Half the skew from 12 units per
+// work-group, all of it from 48.  (Below two units per work-group it has to be zero in any
+// case: the merge pass relies on every work-group between a row's first and last piece holding
+// a piece of it.)
 LAMINA_HD inline int share_skew(bool balanced, unsigned U, unsigned n)
 {
     if (!balanced || U < 12u * n)
         return 0;
-    return U >= 24u * n ? kParitySkew : kParitySkew / 2;
+    return U >= 48u * n ? kParitySkew : kParitySkew / 2;
 }
 LAMINA_HD inline unsigned share_begin(unsigned U, unsigned n, unsigned j, int skew)
 {

@@ -587,12 +587,12 @@ def brute_force_partials(lens, Hkv, G, unit, nwg, parts=None):
     cost = 0 if parts is not None else 1
     owner_of_unit = []
     U = sum(u + cost for u in units) * Hkv
-    # Fixed partitions are dealt evenly.  Balanced shares: with at least 24 units per work-group
+    # Fixed partitions are dealt evenly.  Balanced shares: with at least 48 units per work-group
     # the even-numbered work-groups take 68/64 of an even share and the odd-numbered ones 60/64
-    # (the odd dies of the chip stream slower); with 12 to 24 units it is 66/64 and 62/64;
+    # (the odd dies of the chip stream slower); with 12 to 48 units it is 66/64 and 62/64;
     # below that the dealing is even.  With a skew, work-group j starts at unit
     # floor(U * c(j) / c(nwg)), c(j) = 64 j + skew * (j odd).
-    skew = 0 if parts is not None else (4 if U >= 24 * nwg else (2 if U >= 12 * nwg else 0))
+    skew = 0 if parts is not None else (4 if U >= 48 * nwg else (2 if U >= 12 * nwg else 0))
     if skew == 0:
         q, rem = divmod(U, nwg)
         begin = [j * q + min(j, rem) for j in range(nwg + 1)]
@@ -616,7 +616,8 @@ def brute_force_partials(lens, Hkv, G, unit, nwg, parts=None):
 def test_balanced_shares_follow_the_batch_and_partials_are_counted():
     d = dev()
     w = W.WORKLOADS["llama3_8b_ctx4096"]
-    nwg = min(1024, 2 * torch.cuda.get_device_properties(0).multi_processor_count)
+    # balanced shares run one work-group per compute unit (half of what can be resident)
+    nwg = (min(1024, 2 * torch.cuda.get_device_properties(0).multi_processor_count) + 1) // 2
     op = lamina.DecodeAttention(w.num_q_heads, w.num_kv_heads, max_batch=64, max_seq_len=65536)
     assert (op.num_splits, op.split_tokens) == (0, 128)
     # a skewed batch: one long row is spread over many work-groups, short and empty ones are not cut
@@ -628,7 +629,7 @@ def test_balanced_shares_follow_the_batch_and_partials_are_counted():
     check((out.cpu().double().numpy(), lse.cpu().double().numpy()), oracle_of(b), "bf16_f32")
     n = op.count_partials(lens)
     assert n == brute_force_partials(lens, w.num_kv_heads, 4, 128, nwg) and n > 0
-    # a big uniform batch on the same handle: as many rows as work-groups; the shares differ by
+    # a big uniform batch on the same handle: two rows per work-group; the shares differ by
     # work-group parity, so rows are cut where an even work-group's share runs into the next row
     lens = [8192] * 64
     b = sized("llama3_8b_ctx4096", lens)

@@ -195,10 +195,14 @@ def timeline(args, w, lens, op, step, torch, lamina, W, out_dtype) -> int:
     print("  work-group exit by die class (work-group number mod 8), mean / last:")
     print("    " + "  ".join(f"{x}: {ex[wg % 8 == x].mean():.1f}/{ex[wg % 8 == x].max():.1f}"
                             for x in range(8) if (wg % 8 == x).any()))
-    first = wg < (nwg + 1) // 2
-    if first.any() and (~first).any():
-        print(f"  first work-group on a compute unit (numbers below {(nwg + 1) // 2}) exits at "
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    first = wg < cus
+    if first.any() and (~first).any():                    # two work-groups per compute unit
+        print(f"  first work-group on a compute unit (numbers below {cus}) exits at "
               f"{ex[first].mean():.1f} us on average, the second one at {ex[~first].mean():.1f} us")
+    else:
+        print(f"  one work-group per compute unit ({nwg} in all): exits {ex.min():.1f} .. "
+              f"{ex.max():.1f} us, mean {ex.mean():.1f} us")
     # aggregate progress: every wavefront stamps the start of loop iterations 0..7 and of every
     # fourth one after that (an iteration is two tile slots); progress between stamps is
     # interpolated linearly, so features shorter than one iteration (~9 us in steady state) blur

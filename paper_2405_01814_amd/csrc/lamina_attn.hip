@@ -1613,16 +1613,15 @@ constexpr int kMaxGrid = 1024;
 // (measured with 0..3: one unit is best -- workload 3: 65.4 / 67.6 / 66.9 / 66.5 % of peak).
 constexpr int kRowCostUnits = 1;
 
-// Contexts up to this many tokens are never cut by the library's own choice: one work-group
-// streams such a row in ~15 us, less than cutting it saves once the merge launch is paid.
-constexpr int kShortContext = 1024;
-
 // Partitioning.  num_splits == 1 never cuts a row; num_splits == N > 1 cuts every row into
 // partitions of ceil(max_seq_len / N) tokens (rounded up to a multiple of 256).  Otherwise
-// (0) rows are not cut when that cannot pay for the partial results and the merge launch --
-// short contexts; batches that already hold a row per half (contexts up to 2048) or per whole
-// (up to 4096) of the resident work-groups (measured: 160 rows of 2048 tokens take 32 us uncut,
-// 39 us balanced; a 160 us call loses 3 % to the merge launch alone) -- nor for batches beyond
+// (0) rows are not cut when that cannot pay for the partial results and the merge launch:
+// contexts up to 512 tokens; contexts up to 1024 unless the batch is tiny (one work-group
+// streams such a row in ~15 us; with at most 32 rows the second launch is still the cheaper:
+// 8 rows of 1024 tokens take 14.8 us uncut, 12.6 us balanced); batches that hold a row per
+// quarter (contexts up to 2048) or per third (up to 4096) of the work-groups that can be
+// resident (measured, us uncut / balanced: 128 rows x 2048 tokens 27.7 / 32.3, 64 rows 25.5 /
+// 22.3; 160 rows x 4096 tokens 56.9 / 58.9, 128 rows 49.7 / 48.3) -- nor for batches beyond
 // what the prefix sum in LDS holds; everything else runs balanced: every work-group streams
 // the same share of the call's tokens.
 Plan make_plan(const lamina_attn_config &c)
@@ -1632,9 +1631,10 @@ Plan make_plan(const lamina_attn_config &c)
     pl.unit = 0;
     const long long pairs = (long long)c.max_batch * c.num_kv_heads;
     if (c.num_splits == 1 ||
-        (c.num_splits == 0 && (c.max_batch > kMaxSplitBatch || c.max_seq_len <= kShortContext ||
+        (c.num_splits == 0 && (c.max_batch > kMaxSplitBatch || c.max_seq_len <= 512 ||
+                               (c.max_seq_len <= 1024 && pairs > 32) ||
                                (c.max_seq_len <= 2048 && pairs >= 128) ||
-                               (c.max_seq_len <= 4096 && pairs >= 256)))) {
+                               (c.max_seq_len <= 4096 && pairs >= 160)))) {
         pl.mode = kModeRows;
     } else if (c.num_splits > 1) {
         pl.mode = kModeFixed;
